@@ -1,0 +1,127 @@
+/*
+ * fmha_varlen -- fused multi-head attention over packed, unpadded
+ * variable-length sequences for AMD MI355X (gfx950), forward and backward.
+ *
+ * The operation is the paper's Eq. 1, softmax(Q K^T / sqrt(d_k)) V, applied to
+ * every sequence of a batch and every head on its own, on the paper's unpadded
+ * storage (Section IV-A-1): the batch and sequence dimensions are merged, only
+ * valid tokens are stored, and a prefix-sum array (the paper's batch_offset,
+ * here cu_seqlens) says where each sequence begins.  The backward pass is the
+ * derivative of Eq. 1 (the paper reports backward timings in Section IV-A-2
+ * but prints no formula).
+ *
+ * In place of the paper's length groups run on separate streams and joined
+ * with events (Section IV-A-2), all sequences are cut into tiles, the tiles
+ * are ordered longest sequence first by a small device kernel, and one launch
+ * per direction on the caller's stream consumes that list; stream order then
+ * gives the "after the producer, before the consumer" guarantee the paper
+ * needs events for.
+ *
+ * Conventions
+ *   - Every pointer named "device" is GPU memory owned by the caller; the
+ *     library never allocates, frees or copies to the host, and never
+ *     synchronises: all work is enqueued on `stream` and the call returns.
+ *   - Tensors are token-major: element (t, h, c) of Q is at
+ *     q[t * q_stride + h * 64 + c], 0 <= t < total_tokens, 0 <= h < heads,
+ *     0 <= c < 64, 16-bit elements (IEEE half or bfloat16).  A stride of 0
+ *     means heads * 64 (dense).  Strides are in elements and must be
+ *     multiples of 8; base pointers must be 16-byte aligned.
+ *   - Sequence i owns rows cu_seqlens[i] .. cu_seqlens[i+1]-1.  Rows of
+ *     different sequences never interact.  Empty sequences are allowed.
+ *   - Inputs are read-only.  Outputs are fully overwritten for all rows.
+ *   - Arithmetic: 16-bit operands, fp32 accumulation and fp32 softmax state;
+ *     the probabilities are rounded to the operand type before they are
+ *     multiplied with V (and dO), as is dS before it meets K and Q.
+ *   - Errors are return codes; fmha_last_error() gives a message for the last
+ *     failing call on the calling thread.  Validation reads only host memory.
+ */
+#ifndef FMHA_VARLEN_H_
+#define FMHA_VARLEN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FMHA_OK = 0,
+  FMHA_ERR_INVALID_ARG = 1, /* null / misaligned pointer, bad size, bad stride, bad prefix sums */
+  FMHA_ERR_UNSUPPORTED = 2, /* head_dim != 64, unknown dtype */
+  FMHA_ERR_WORKSPACE = 3,   /* workspace missing or smaller than fmha_varlen_workspace_size() */
+  FMHA_ERR_HIP = 4          /* a HIP launch failed */
+} fmha_status_t;
+
+typedef enum { FMHA_F16 = 0, FMHA_BF16 = 1 } fmha_dtype_t;
+
+/* The workspace already holds the tile list for exactly this cu_seqlens /
+ * seqused / batch: skip rebuilding it.  A training step calls attention once
+ * per layer and direction with the same batch, as the paper computes its
+ * batch_offset once per mini-batch (Section IV-B-2). */
+#define FMHA_FLAG_REUSE_SCHEDULE 1u
+
+typedef struct fmha_varlen_params {
+  int32_t batch;        /* number of sequences B >= 0 */
+  int32_t total_tokens; /* T = cu_seqlens[B] */
+  int32_t heads;        /* H >= 1 */
+  int32_t head_dim;     /* must be 64 */
+  int32_t max_seqlen;   /* upper bound on the longest sequence; only sizes the launch.  A longer
+                           sequence is still computed correctly if max_seqlen <= 0 is passed
+                           (no bound assumed); a positive value that is too small is an error
+                           when cu_seqlens_host is given and undefined work loss otherwise */
+  int32_t dtype;        /* fmha_dtype_t */
+  uint32_t flags;       /* FMHA_FLAG_* */
+  float scale;          /* multiplies Q K^T; 1/sqrt(64) = 0.125 for Eq. 1 */
+  int64_t q_stride, k_stride, v_stride, o_stride;     /* elements between tokens, 0 = dense */
+  int64_t do_stride, dq_stride, dk_stride, dv_stride; /* backward only, 0 = dense */
+  const int32_t* cu_seqlens;      /* device, B+1 entries, cu[0] = 0, non-decreasing */
+  const int32_t* cu_seqlens_host; /* optional host copy: lets the call validate the prefix sums */
+  const int32_t* seqused;         /* optional device, B entries: only keys j < seqused[i] of
+                                     sequence i are attended (padded layout with a key mask);
+                                     NULL = all L_i keys.  All L_i query rows are computed. */
+  void* workspace;                /* device, 256-byte aligned, see fmha_varlen_workspace_size */
+  size_t workspace_bytes;
+} fmha_varlen_params_t;
+
+/* Bytes of device workspace for a batch of this shape (tile list; plus, if
+ * need_bwd, one fp32 per (token, head) for the row sums of dO o O).  Pure
+ * host arithmetic; returns 0 on invalid sizes. */
+size_t fmha_varlen_workspace_size(int32_t batch, int32_t total_tokens, int32_t heads,
+                                  int32_t need_bwd);
+
+/* Forward: O = softmax(scale * Q K^T) V per sequence and head (Eq. 1).
+ *   q, k, v : device, [T, H, 64] with the strides in p (read)
+ *   o       : device, [T, H, 64] (written)
+ *   lse     : device, fp32 [H, T]: natural-log sum of exp of the scaled scores of each row
+ *             (written; needed by the backward call)
+ *   stream  : hipStream_t (NULL = default stream)
+ * Returns an fmha_status_t. */
+int fmha_varlen_fwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
+                    void* o, float* lse, void* stream);
+
+/* Backward: given dO, recompute the probabilities from q, k and lse and write
+ *   dV = P^T dO,  dP = dO V^T,  dS = P o (dP - rowsum(dO o O)),
+ *   dQ = scale dS K,  dK = scale dS^T Q.
+ *   q, k, v, o, d_o : device [T, H, 64] (read);  lse : device fp32 [H, T] from the forward call
+ *   dq, dk, dv      : device [T, H, 64] (written; rows of keys masked by seqused get zeros)
+ * Needs a workspace sized with need_bwd = 1. */
+int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
+                    const void* o, const void* d_o, const float* lse, void* dq, void* dk,
+                    void* dv, void* stream);
+
+/* Number of 128-row tiles the schedule holds at most for this shape (host
+ * arithmetic, the launch is sized by it), and a device-to-host-free way for
+ * tests to locate the tile list inside the workspace: the list starts at byte
+ * offset *list_offset, holds int32 pairs (sequence, first row within it), and
+ * its length is the int32 at byte offset *count_offset. */
+int32_t fmha_varlen_schedule_info(int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                                  size_t* count_offset, size_t* list_offset);
+
+/* Message for the last error returned on this thread ("" if none). */
+const char* fmha_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FMHA_VARLEN_H_ */

@@ -1,0 +1,246 @@
+// Host side of the C ABI declared in include/fmha_varlen.h: argument checks
+// (host memory only), workspace carving, and the launches.  One launch per
+// direction and kernel on the caller's stream; nothing here allocates,
+// copies to the host or waits for the device.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/fmha_varlen.h"
+#include "bwd_kernels.h"
+#include "fwd_kernel.h"
+#include "schedule.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+constexpr size_t kAlign = 256;
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Tiles of 128 rows: sum_i ceil(L_i/128) <= T/128 + B for any lengths.
+int64_t tile_capacity(int64_t batch, int64_t total_tokens) {
+  return total_tokens / fmha::kTileRows + batch;
+}
+
+struct Workspace {
+  int32_t* count;
+  fmha::TileItem* list;
+  float* dsum;
+  size_t count_off, list_off, dsum_off, bytes_fwd, bytes_bwd;
+};
+
+Workspace carve(void* base, int64_t batch, int64_t total_tokens, int64_t heads) {
+  Workspace w;
+  w.count_off = 0;
+  w.list_off = kAlign;
+  const size_t list_bytes = sizeof(fmha::TileItem) * (size_t)(tile_capacity(batch, total_tokens) + 1);
+  w.dsum_off = round_up(w.list_off + list_bytes, kAlign);
+  w.bytes_fwd = w.dsum_off;
+  w.bytes_bwd = w.dsum_off + round_up(sizeof(float) * (size_t)total_tokens * (size_t)heads, kAlign);
+  char* b = static_cast<char*>(base);
+  w.count = reinterpret_cast<int32_t*>(b + w.count_off);
+  w.list = reinterpret_cast<fmha::TileItem*>(b + w.list_off);
+  w.dsum = reinterpret_cast<float*>(b + w.dsum_off);
+  return w;
+}
+
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+int check_stride(const char* name, int64_t s, int64_t dense, int64_t* out) {
+  if (s == 0) s = dense;
+  if (s < dense || (s & 7)) return fail(FMHA_ERR_INVALID_ARG, "%s_stride=%lld must be 0 or a multiple of 8 that is >= heads*64=%lld",
+                                        name, (long long)s, (long long)dense);
+  *out = s;
+  return FMHA_OK;
+}
+
+int check_common(const fmha_varlen_params_t* p, bool bwd) {
+  if (!p) return fail(FMHA_ERR_INVALID_ARG, "params is null");
+  if (p->head_dim != fmha::kHeadDim) return fail(FMHA_ERR_UNSUPPORTED, "head_dim=%d, only 64 is supported", p->head_dim);
+  if (p->dtype != FMHA_F16 && p->dtype != FMHA_BF16) return fail(FMHA_ERR_UNSUPPORTED, "dtype=%d is neither FMHA_F16 nor FMHA_BF16", p->dtype);
+  if (p->batch < 0) return fail(FMHA_ERR_INVALID_ARG, "batch=%d is negative", p->batch);
+  if (p->total_tokens < 0) return fail(FMHA_ERR_INVALID_ARG, "total_tokens=%d is negative", p->total_tokens);
+  if (p->heads <= 0) return fail(FMHA_ERR_INVALID_ARG, "heads=%d must be positive", p->heads);
+  if ((int64_t)p->total_tokens * p->heads > (int64_t)1 << 40) return fail(FMHA_ERR_INVALID_ARG, "total_tokens*heads too large");
+  if (!(p->scale == p->scale) || p->scale - p->scale != 0.f) return fail(FMHA_ERR_INVALID_ARG, "scale is not finite");
+  if (!p->cu_seqlens) return fail(FMHA_ERR_INVALID_ARG, "cu_seqlens is null");
+  if (misaligned(p->cu_seqlens, 4) || (p->seqused && misaligned(p->seqused, 4)))
+    return fail(FMHA_ERR_INVALID_ARG, "cu_seqlens/seqused must be 4-byte aligned");
+  if (p->cu_seqlens_host) {
+    const int32_t* cu = p->cu_seqlens_host;
+    if (cu[0] != 0) return fail(FMHA_ERR_INVALID_ARG, "cu_seqlens_host[0]=%d, expected 0", cu[0]);
+    for (int i = 0; i < p->batch; i++) {
+      if (cu[i + 1] < cu[i]) return fail(FMHA_ERR_INVALID_ARG, "cu_seqlens_host decreases at %d (%d -> %d)", i, cu[i], cu[i + 1]);
+      if (p->max_seqlen > 0 && cu[i + 1] - cu[i] > p->max_seqlen)
+        return fail(FMHA_ERR_INVALID_ARG, "sequence %d has %d tokens, more than max_seqlen=%d", i, cu[i + 1] - cu[i], p->max_seqlen);
+    }
+    if (cu[p->batch] != p->total_tokens)
+      return fail(FMHA_ERR_INVALID_ARG, "cu_seqlens_host[batch]=%d differs from total_tokens=%d", cu[p->batch], p->total_tokens);
+  }
+  const size_t need = fmha_varlen_workspace_size(p->batch, p->total_tokens, p->heads, bwd);
+  if (!p->workspace) return fail(FMHA_ERR_WORKSPACE, "workspace is null (%zu bytes needed)", need);
+  if (misaligned(p->workspace, kAlign)) return fail(FMHA_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (p->workspace_bytes < need) return fail(FMHA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", p->workspace_bytes, need);
+  return FMHA_OK;
+}
+
+int check_ptr(const char* name, const void* ptr) {
+  if (!ptr) return fail(FMHA_ERR_INVALID_ARG, "%s is null", name);
+  if (misaligned(ptr, 16)) return fail(FMHA_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+  return FMHA_OK;
+}
+
+// Workgroups launched: one per (tile, head) that can exist.  max_seqlen, when
+// given, tightens the bound; the kernels stride over the list, so a bound
+// that is too small costs time, never correctness.
+unsigned grid_for(const fmha_varlen_params_t* p) {
+  int64_t tiles = tile_capacity(p->batch, p->total_tokens);
+  if (p->max_seqlen > 0) {
+    const int64_t per_seq = (p->max_seqlen + fmha::kTileRows - 1) / fmha::kTileRows;
+    if (per_seq * p->batch < tiles) tiles = per_seq * p->batch;
+  }
+  int64_t g = tiles * p->heads;
+  if (g < 1) g = 1;
+  if (g > (1 << 22)) g = 1 << 22;
+  return (unsigned)g;
+}
+
+int launch_schedule(const fmha_varlen_params_t* p, const Workspace& w, hipStream_t st) {
+  if (p->flags & FMHA_FLAG_REUSE_SCHEDULE) return FMHA_OK;
+  const int cap = (int)tile_capacity(p->batch, p->total_tokens);
+  fmha::schedule_kernel<<<1, fmha::kSchedThreads, 0, st>>>(p->cu_seqlens, p->seqused, p->batch, w.count, w.list, cap);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FMHA_ERR_HIP, "schedule launch failed: %s", hipGetErrorString(e));
+  return FMHA_OK;
+}
+
+fmha::Problem problem_of(const fmha_varlen_params_t* p, const Workspace& w) {
+  fmha::Problem pb;
+  pb.cu = p->cu_seqlens;
+  pb.seqused = p->seqused;
+  pb.n_tiles = w.count;
+  pb.tiles = w.list;
+  pb.heads = p->heads;
+  pb.total_tokens = p->total_tokens;
+  pb.scale = p->scale;
+  return pb;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fmha_last_error(void) { return g_err; }
+
+size_t fmha_varlen_workspace_size(int32_t batch, int32_t total_tokens, int32_t heads, int32_t need_bwd) {
+  if (batch < 0 || total_tokens < 0 || heads <= 0) return 0;
+  Workspace w = carve(nullptr, batch, total_tokens, heads);
+  return need_bwd ? w.bytes_bwd : w.bytes_fwd;
+}
+
+int32_t fmha_varlen_schedule_info(int32_t batch, int32_t total_tokens, int32_t max_seqlen,
+                                  size_t* count_offset, size_t* list_offset) {
+  if (batch < 0 || total_tokens < 0) return -1;
+  Workspace w = carve(nullptr, batch, total_tokens, 1);
+  if (count_offset) *count_offset = w.count_off;
+  if (list_offset) *list_offset = w.list_off;
+  (void)max_seqlen;
+  return (int32_t)tile_capacity(batch, total_tokens);
+}
+
+int fmha_varlen_fwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
+                    void* o, float* lse, void* stream) {
+  int rc = check_common(p, false);
+  if (rc) return rc;
+  if ((rc = check_ptr("q", q)) || (rc = check_ptr("k", k)) || (rc = check_ptr("v", v)) ||
+      (rc = check_ptr("o", o)) || (rc = check_ptr("lse", lse)))
+    return rc;
+  const int64_t dense = (int64_t)p->heads * fmha::kHeadDim;
+  fmha::FwdArgs a;
+  if ((rc = check_stride("q", p->q_stride, dense, &a.q_stride)) ||
+      (rc = check_stride("k", p->k_stride, dense, &a.k_stride)) ||
+      (rc = check_stride("v", p->v_stride, dense, &a.v_stride)) ||
+      (rc = check_stride("o", p->o_stride, dense, &a.o_stride)))
+    return rc;
+  g_err[0] = 0;
+  if (p->batch == 0 || p->total_tokens == 0) return FMHA_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Workspace w = carve(p->workspace, p->batch, p->total_tokens, p->heads);
+  if ((rc = launch_schedule(p, w, st))) return rc;
+  a.pb = problem_of(p, w);
+  a.q = static_cast<const uint16_t*>(q);
+  a.k = static_cast<const uint16_t*>(k);
+  a.v = static_cast<const uint16_t*>(v);
+  a.o = static_cast<uint16_t*>(o);
+  a.lse = lse;
+  const unsigned grid = grid_for(p);
+  if (p->dtype == FMHA_F16)
+    fmha::fmha_fwd_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
+  else
+    fmha::fmha_fwd_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FMHA_ERR_HIP, "forward launch failed: %s", hipGetErrorString(e));
+  return FMHA_OK;
+}
+
+int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
+                    const void* o, const void* d_o, const float* lse, void* dq, void* dk,
+                    void* dv, void* stream) {
+  int rc = check_common(p, true);
+  if (rc) return rc;
+  if ((rc = check_ptr("q", q)) || (rc = check_ptr("k", k)) || (rc = check_ptr("v", v)) ||
+      (rc = check_ptr("o", o)) || (rc = check_ptr("d_o", d_o)) || (rc = check_ptr("lse", lse)) ||
+      (rc = check_ptr("dq", dq)) || (rc = check_ptr("dk", dk)) || (rc = check_ptr("dv", dv)))
+    return rc;
+  const int64_t dense = (int64_t)p->heads * fmha::kHeadDim;
+  fmha::BwdArgs a;
+  if ((rc = check_stride("q", p->q_stride, dense, &a.q_stride)) ||
+      (rc = check_stride("k", p->k_stride, dense, &a.k_stride)) ||
+      (rc = check_stride("v", p->v_stride, dense, &a.v_stride)) ||
+      (rc = check_stride("o", p->o_stride, dense, &a.o_stride)) ||
+      (rc = check_stride("do", p->do_stride, dense, &a.do_stride)) ||
+      (rc = check_stride("dq", p->dq_stride, dense, &a.dq_stride)) ||
+      (rc = check_stride("dk", p->dk_stride, dense, &a.dk_stride)) ||
+      (rc = check_stride("dv", p->dv_stride, dense, &a.dv_stride)))
+    return rc;
+  g_err[0] = 0;
+  if (p->batch == 0 || p->total_tokens == 0) return FMHA_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Workspace w = carve(p->workspace, p->batch, p->total_tokens, p->heads);
+  if ((rc = launch_schedule(p, w, st))) return rc;
+  a.pb = problem_of(p, w);
+  a.q = static_cast<const uint16_t*>(q);
+  a.k = static_cast<const uint16_t*>(k);
+  a.v = static_cast<const uint16_t*>(v);
+  a.o = static_cast<const uint16_t*>(o);
+  a.d_o = static_cast<const uint16_t*>(d_o);
+  a.lse = lse;
+  a.dsum = w.dsum;
+  a.dq = static_cast<uint16_t*>(dq);
+  a.dk = static_cast<uint16_t*>(dk);
+  a.dv = static_cast<uint16_t*>(dv);
+  const unsigned grid = grid_for(p);
+  if (p->dtype == FMHA_F16) {
+    fmha::bwd_dq_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
+    fmha::bwd_dkv_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
+  } else {
+    fmha::bwd_dq_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
+    fmha::bwd_dkv_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FMHA_ERR_HIP, "backward launch failed: %s", hipGetErrorString(e));
+  return FMHA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,58 @@
+// Tile list: the replacement for the paper's length groups and per-group
+// streams (Section IV-A-2).  Every sequence is cut into 128-row tiles; tiles
+// are emitted longest sequence first so that one launch, whose workgroups the
+// hardware hands out in index order, finishes the expensive tiles early and
+// fills the tail with cheap ones.
+#pragma once
+#include "kernel_args.h"
+
+namespace fmha {
+
+constexpr int kSchedThreads = 1024;
+constexpr int kSchedBuckets = 128;  // bucket = ceil(keys / 8), clipped; bucket 0 = longest
+
+__device__ __forceinline__ int sched_bucket(int nkeys) {
+  int b = (nkeys + 7) >> 3;
+  b = b > kSchedBuckets - 1 ? kSchedBuckets - 1 : b;
+  return kSchedBuckets - 1 - b;
+}
+
+// One workgroup.  count <- number of tiles, list[0..count) <- tiles.  `cap`
+// bounds the list (total_tokens/128 + batch always suffices).
+__global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* __restrict__ cu,
+                                                                 const int32_t* __restrict__ seqused,
+                                                                 int batch, int32_t* count,
+                                                                 TileItem* list, int cap) {
+  __shared__ int cursor[kSchedBuckets];
+  const int tid = threadIdx.x;
+  if (tid < kSchedBuckets) cursor[tid] = 0;
+  __syncthreads();
+  for (int i = tid; i < batch; i += kSchedThreads) {
+    const int len = cu[i + 1] - cu[i];
+    if (len <= 0) continue;
+    int nk = seqused ? min(seqused[i], len) : len;
+    atomicAdd(&cursor[sched_bucket(nk)], (len + kTileRows - 1) / kTileRows);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    for (int b = 0; b < kSchedBuckets; b++) {
+      int n = cursor[b];
+      cursor[b] = run;
+      run += n;
+    }
+    *count = run < cap ? run : cap;
+  }
+  __syncthreads();
+  for (int i = tid; i < batch; i += kSchedThreads) {
+    const int len = cu[i + 1] - cu[i];
+    if (len <= 0) continue;
+    int nk = seqused ? min(seqused[i], len) : len;
+    const int nt = (len + kTileRows - 1) / kTileRows;
+    int at = atomicAdd(&cursor[sched_bucket(nk)], nt);
+    for (int t = 0; t < nt; t++)
+      if (at + t < cap) list[at + t] = TileItem{i, t * kTileRows};
+  }
+}
+
+}  // namespace fmha

@@ -1,0 +1,159 @@
+"""ctypes binding of libfmha_varlen.so (see include/fmha_varlen.h).
+
+Argument marshalling only: every step of the path runs in the HIP library.
+torch is used for device memory and the current stream.  There is no CPU
+fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfmha_varlen.so")
+
+FMHA_OK, FMHA_ERR_INVALID_ARG, FMHA_ERR_UNSUPPORTED, FMHA_ERR_WORKSPACE, FMHA_ERR_HIP = range(5)
+FMHA_F16, FMHA_BF16 = 0, 1
+FMHA_FLAG_REUSE_SCHEDULE = 1
+
+EXPORTS = ("fmha_varlen_workspace_size", "fmha_varlen_fwd", "fmha_varlen_bwd",
+           "fmha_varlen_schedule_info", "fmha_last_error")
+
+
+class Params(ctypes.Structure):
+    """Mirror of fmha_varlen_params_t."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("total_tokens", ctypes.c_int32), ("heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("max_seqlen", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("flags", ctypes.c_uint32), ("scale", ctypes.c_float),
+        ("q_stride", ctypes.c_int64), ("k_stride", ctypes.c_int64),
+        ("v_stride", ctypes.c_int64), ("o_stride", ctypes.c_int64),
+        ("do_stride", ctypes.c_int64), ("dq_stride", ctypes.c_int64),
+        ("dk_stride", ctypes.c_int64), ("dv_stride", ctypes.c_int64),
+        ("cu_seqlens", ctypes.c_void_p), ("cu_seqlens_host", ctypes.c_void_p),
+        ("seqused", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
+        ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+class FmhaError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"fmha_varlen error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2208_08124_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp = ctypes.c_void_p
+        L.fmha_varlen_workspace_size.argtypes = [ctypes.c_int32] * 4
+        L.fmha_varlen_workspace_size.restype = ctypes.c_size_t
+        L.fmha_varlen_fwd.argtypes = [ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp]
+        L.fmha_varlen_fwd.restype = ctypes.c_int
+        L.fmha_varlen_bwd.argtypes = [ctypes.POINTER(Params)] + [vp] * 10
+        L.fmha_varlen_bwd.restype = ctypes.c_int
+        L.fmha_varlen_schedule_info.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_size_t)] * 2
+        L.fmha_varlen_schedule_info.restype = ctypes.c_int32
+        L.fmha_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().fmha_last_error().decode()
+
+
+def _check(rc):
+    if rc != FMHA_OK:
+        raise FmhaError(rc, last_error())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return FMHA_F16
+    if t.dtype == torch.bfloat16:
+        return FMHA_BF16
+    raise FmhaError(FMHA_ERR_UNSUPPORTED, f"dtype {t.dtype}")
+
+
+def _tok_stride(t: torch.Tensor) -> int:
+    assert t.dim() == 3 and t.stride(2) == 1 and t.stride(1) == t.shape[2], \
+        "tensors are [T, H, 64] with heads contiguous inside a token"
+    return t.stride(0) if t.shape[0] > 1 else t.shape[1] * t.shape[2]
+
+
+def fmha_varlen_workspace_size(batch: int, total_tokens: int, heads: int, need_bwd: bool) -> int:
+    return int(lib().fmha_varlen_workspace_size(batch, total_tokens, heads, int(need_bwd)))
+
+
+def fmha_varlen_schedule_info(batch: int, total_tokens: int, max_seqlen: int = 0):
+    """(capacity in tiles, byte offset of the count, byte offset of the list)."""
+    c, l = ctypes.c_size_t(), ctypes.c_size_t()
+    cap = lib().fmha_varlen_schedule_info(batch, total_tokens, max_seqlen, ctypes.byref(c), ctypes.byref(l))
+    return int(cap), int(c.value), int(l.value)
+
+
+def alloc_workspace(batch: int, total_tokens: int, heads: int, need_bwd: bool, device="cuda"):
+    n = max(fmha_varlen_workspace_size(batch, total_tokens, heads, need_bwd), 256)
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host, reuse_schedule):
+    p = Params()
+    p.batch = cu_seqlens.numel() - 1
+    p.total_tokens, p.heads, p.head_dim = q.shape
+    p.max_seqlen = int(max_seqlen)
+    p.dtype = _dtype_code(q)
+    p.flags = FMHA_FLAG_REUSE_SCHEDULE if reuse_schedule else 0
+    p.scale = float(scale)
+    assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_cuda and cu_seqlens.is_contiguous()
+    p.cu_seqlens = cu_seqlens.data_ptr()
+    keep = []
+    if cu_seqlens_host is not None:
+        h = cu_seqlens_host.to(dtype=torch.int32, device="cpu").contiguous()
+        keep.append(h)
+        p.cu_seqlens_host = h.data_ptr()
+    if seqused is not None:
+        assert seqused.dtype == torch.int32 and seqused.is_cuda and seqused.is_contiguous()
+        p.seqused = seqused.data_ptr()
+    p.workspace = workspace.data_ptr()
+    p.workspace_bytes = workspace.numel() * workspace.element_size()
+    return p, keep
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def fmha_varlen_fwd(q, k, v, cu_seqlens, max_seqlen, scale, o, lse, workspace, *,
+                    seqused=None, cu_seqlens_host=None, reuse_schedule=False):
+    """Enqueue the forward pass on torch's current stream; fills `o` and `lse` ([H, T] fp32)."""
+    p, keep = _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host, reuse_schedule)
+    p.q_stride, p.k_stride, p.v_stride, p.o_stride = map(_tok_stride, (q, k, v, o))
+    assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.numel() == q.shape[0] * q.shape[1]
+    _check(lib().fmha_varlen_fwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                 o.data_ptr(), lse.data_ptr(), _stream()))
+    del keep
+
+
+def fmha_varlen_bwd(q, k, v, o, d_o, lse, cu_seqlens, max_seqlen, scale, dq, dk, dv, workspace, *,
+                    seqused=None, cu_seqlens_host=None, reuse_schedule=False):
+    """Enqueue the backward pass on torch's current stream; fills dq, dk, dv."""
+    p, keep = _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host, reuse_schedule)
+    p.q_stride, p.k_stride, p.v_stride, p.o_stride = map(_tok_stride, (q, k, v, o))
+    p.do_stride, p.dq_stride, p.dk_stride, p.dv_stride = map(_tok_stride, (d_o, dq, dk, dv))
+    _check(lib().fmha_varlen_bwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
+                                 o.data_ptr(), d_o.data_ptr(), lse.data_ptr(), dq.data_ptr(),
+                                 dk.data_ptr(), dv.data_ptr(), _stream()))
+    del keep

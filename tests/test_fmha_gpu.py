@@ -1,0 +1,176 @@
+"""Parity of the HIP path (through the C ABI) against the fp64 oracle.
+
+Tolerances (the task's stated bar): outputs within 5e-3 max-abs of the oracle;
+each gradient tensor within 1e-2 of the oracle relative to that tensor's
+largest magnitude.  For bfloat16 the stored output's own rounding (half an
+ulp at the value) is allowed on top, because it alone can exceed 5e-3.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2208_08124_amd import fmha
+from paper_2208_08124_amd import workloads as wl
+from gpu_util import DeviceBatch, oracle_inputs, to_f64, ulp_half
+
+pytestmark = pytest.mark.gpu
+
+O_TOL = 5e-3
+G_TOL = 1e-2
+G_FLOOR = 0.1
+
+
+def check_forward(b, db):
+    x = oracle_inputs(b)
+    o_ref, lse_ref = oracle.fwd(x["q"], x["k"], x["v"], b["cu_seqlens"], b["scale"], b.get("seqused"))
+    o = to_f64(db.o)
+    lse = to_f64(db.lse)
+    assert not np.isnan(o).any() and not np.isnan(lse).any(), "rows left unwritten"
+    extra = ulp_half(o_ref, b["dtype"]) if b["dtype"] == "bf16" else 0.0
+    err = np.abs(o - o_ref)
+    assert (err <= O_TOL + extra).all(), f"max |O - O_ref| = {err.max():.3e}"
+    fin = np.isfinite(lse_ref)
+    assert np.array_equal(np.isfinite(lse), fin)
+    assert np.abs(lse[fin] - lse_ref[fin]).max() <= 1e-3 * max(1.0, np.abs(lse_ref[fin]).max())
+    return float(err.max())
+
+
+def check_backward(b, db):
+    x = oracle_inputs(b)
+    ref = oracle.bwd(x["q"], x["k"], x["v"], x["do"], b["cu_seqlens"], b["scale"], b.get("seqused"))
+    out = {}
+    for name, got, want in zip(("dq", "dk", "dv"), (db.dq, db.dk, db.dv), ref):
+        g = to_f64(got)
+        assert not np.isnan(g).any(), f"{name}: rows left unwritten"
+        # a gradient that vanishes by exact cancellation (L = 1, constant V) leaves
+        # only the 16-bit rounding of O inside D: measure it against 0.1, not against 0
+        denom = max(np.abs(want).max(), G_FLOOR)
+        rel = np.abs(g - want).max() / denom
+        assert rel <= G_TOL, f"{name}: max-abs error / max|ref| = {rel:.3e}"
+        out[name] = float(rel)
+    return out
+
+
+def run(b, need_bwd):
+    db = DeviceBatch(b, need_bwd)
+    db.fwd(cu_seqlens_host=torch.from_numpy(b["cu_seqlens"]))
+    torch.cuda.synchronize()
+    check_forward(b, db)
+    if need_bwd:
+        db.bwd(reuse_schedule=True)
+        torch.cuda.synchronize()
+        check_backward(b, db)
+    return db
+
+
+def test_config1_tiny_forward():
+    b = wl.make_workload(1)
+    run(b, False)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("lengths", [
+    [1], [2, 1, 3], [31, 32, 33], [63, 64, 65], [127, 128, 129], [200, 5, 77, 300],
+    [512, 1, 511, 257], [0, 40, 0, 0, 7, 0], [640, 130],
+])
+def test_ragged_lengths_fwd_bwd(lengths, dtype):
+    b = wl.make_batch(lengths, 3, dtype, seed=sum(lengths) + len(lengths))
+    run(b, True)
+
+
+def test_config3_bert_large_fwd_bwd():
+    b = wl.make_workload(3)
+    run(b, True)
+
+
+def test_config4_skewed_fwd_bwd():
+    b = wl.make_workload(4)
+    run(b, True)
+
+
+def test_scales_and_heads():
+    for heads, scale in ((1, 1.0), (5, 0.05), (16, 0.125), (2, 0.0), (2, -0.2)):
+        b = wl.make_batch([70, 9, 150], heads, "f16", seed=heads, scale=scale)
+        run(b, True)
+
+
+def test_schedule_covers_every_tile_once_longest_first():
+    lengths = wl.draw_lengths(4, np.random.default_rng(3))
+    b = wl.make_batch(lengths, 1, "f16", seed=5, backward=False)
+    db = DeviceBatch(b, False)
+    db.fwd()
+    torch.cuda.synchronize()
+    cap, c_off, l_off = fmha.fmha_varlen_schedule_info(b["batch"], b["total_tokens"])
+    ws = db.ws.cpu().numpy()
+    n = int(ws[c_off:c_off + 4].view(np.int32)[0])
+    items = ws[l_off:l_off + 8 * n].view(np.int32).reshape(n, 2)
+    want = {(i, r) for i, L in enumerate(lengths) for r in range(0, L, 128)}
+    got = [tuple(x) for x in items.tolist()]
+    assert n <= cap and len(got) == len(set(got)) and set(got) == want
+    bucket = np.minimum((lengths[items[:, 0]] + 7) // 8, 127)
+    assert (np.diff(bucket) <= 0).all(), "tiles are not ordered longest sequence first"
+
+
+def test_padded_layout_with_key_mask_matches_packed():
+    b = wl.make_batch([5, 130, 64, 1, 77], 2, "f16", seed=11)
+    db = run(b, True)
+    p = wl.pad_batch(b, 192)
+    dp = run(p, True)
+    rows = torch.from_numpy(wl.valid_row_index(b["lengths"], 192)).cuda()
+    assert torch.equal(dp.o[rows], db.o)
+    assert torch.equal(dp.lse[:, rows], db.lse)
+    # the padded call's pad rows carry zero dO, so the valid rows see the same sums
+    for a_, b_ in ((dp.dq, db.dq), (dp.dk, db.dk), (dp.dv, db.dv)):
+        assert torch.equal(a_[rows], b_)
+    mask = torch.ones(p["total_tokens"], dtype=torch.bool, device="cuda")
+    mask[rows] = False
+    assert not dp.dk[mask].any() and not dp.dv[mask].any()
+
+
+def test_strided_interleaved_qkv_and_determinism():
+    b = wl.make_batch([100, 260, 33], 4, "f16", seed=21)
+    db = run(b, True)
+    # same data inside one [T, 3, H, 64] buffer: token stride 3*H*64
+    qkv = torch.stack([db.q, db.k, db.v], dim=1).contiguous()
+    d2 = DeviceBatch(b, True)
+    d2.q, d2.k, d2.v = qkv[:, 0], qkv[:, 1], qkv[:, 2]
+    grads = torch.full_like(qkv, float("nan"))
+    d2.dq, d2.dk, d2.dv = grads[:, 0], grads[:, 1], grads[:, 2]
+    d2.fwd()
+    d2.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    for x, y in ((d2.o, db.o), (d2.lse, db.lse), (d2.dq, db.dq), (d2.dk, db.dk), (d2.dv, db.dv)):
+        assert torch.equal(x, y)
+
+
+def test_stream_order_without_host_sync():
+    """Producer -> attention -> consumer on a side stream, no host waits in between."""
+    b = wl.make_batch([300, 45], 2, "f16", seed=31, backward=False)
+    ref = run(b, False)
+    db = DeviceBatch(b, False)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        staged = torch.full_like(db.q, float("nan"))
+        staged.copy_(db.q)         # producer: q only becomes valid on this stream
+        db.q = staged
+        db.fwd()
+        total = db.o.float().sum()  # consumer
+    s.synchronize()
+    assert torch.equal(db.o, ref.o)
+    assert total.item() == ref.o.float().sum().item()
+
+
+def test_error_codes_need_no_device_work():
+    b = wl.make_batch([8, 8], 2, "f16", seed=1, backward=False)
+    db = DeviceBatch(b, False)
+    bad = torch.tensor([0, 9, 16], dtype=torch.int32)
+    with pytest.raises(fmha.FmhaError) as e:
+        db.fwd(cu_seqlens_host=torch.tensor([0, 9, 8], dtype=torch.int32))
+    assert e.value.code == fmha.FMHA_ERR_INVALID_ARG
+    small = db.ws[:16]
+    with pytest.raises(fmha.FmhaError) as e:
+        fmha.fmha_varlen_fwd(db.q, db.k, db.v, db.cu, 8, 0.125, db.o, db.lse, small)
+    assert e.value.code == fmha.FMHA_ERR_WORKSPACE
+    del bad
