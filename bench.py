@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed variable-length attention hot path on one MI355X.
+
+A step = one pass of the whole path over one synthetic batch: tile-list build
++ forward + backward (dQ pass, dK/dV pass), inputs resident in HBM.  The
+workload is the BERT-large fwd+bwd batch (56 sequences, 16 heads, d = 64,
+max length 512, seeded length mixture; fp16).  Prints ONE JSON line.
+
+Useful FLOPs count only real tokens and the five backward contractions:
+forward 4*sum(L^2)*H*d, backward 10*sum(L^2)*H*d.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # MI355X dense MFMA, published
+HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="workload 2..5 (3 = headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-padded", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+              "(see DESIGN.md, 'More than one GPU')" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2208_08124_amd import fmha
+    from paper_2208_08124_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    fmha.lib()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    dev_dt = {"f16": torch.float16, "bf16": torch.bfloat16}
+
+    b = wl.make_workload(args.config, backward=True)
+    dt = b["dtype"]
+    lengths = b["lengths"]
+    T, H = b["total_tokens"], b["heads"]
+    sum_l2 = float((lengths.astype(np.float64) ** 2).sum())
+    fl_fwd = 4.0 * sum_l2 * H * 64
+    fl_dq = 2.0 * sum_l2 * H * 64    # of the dQ pass only dQ = dS K is new work
+    fl_dkv = 8.0 * sum_l2 * H * 64   # S, dP, dV, dK
+    fl_all = fl_fwd + fl_dq + fl_dkv
+
+    def dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(dev_dt[dt])
+
+    class Dev:
+        def __init__(self, bb):
+            self.bb = bb
+            self.q, self.k, self.v, self.do = (dev(bb[n]) for n in ("q", "k", "v", "do"))
+            self.cu = torch.from_numpy(bb["cu_seqlens"]).cuda()
+            self.su = torch.from_numpy(bb["seqused"]).cuda() if "seqused" in bb else None
+            t = bb["total_tokens"]
+            self.o = torch.empty_like(self.q)
+            self.lse = torch.empty((H, t), dtype=torch.float32, device="cuda")
+            self.dq, self.dk, self.dv = (torch.empty_like(self.q) for _ in range(3))
+            self.ws = fmha.alloc_workspace(bb["batch"], t, H, True)
+
+        def fwd(self, reuse=False):
+            fmha.fmha_varlen_fwd(self.q, self.k, self.v, self.cu, self.bb["max_seqlen"], self.bb["scale"],
+                                 self.o, self.lse, self.ws, seqused=self.su, reuse_schedule=reuse)
+
+        def bwd(self, only=None):
+            fmha.fmha_varlen_bwd(self.q, self.k, self.v, self.o, self.do, self.lse, self.cu,
+                                 self.bb["max_seqlen"], self.bb["scale"], self.dq, self.dk, self.dv,
+                                 self.ws, seqused=self.su, reuse_schedule=True, only=only)
+
+        def step(self):
+            self.fwd()      # builds the tile list, then the forward kernel
+            self.bwd()      # reuses the list: dQ pass + dK/dV pass
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    d = Dev(b)
+    sec = timed(d.step, args.steps, args.warmup)
+
+    # per-kernel durations: HIP events on the launch stream around single-kernel calls
+    def kernel_ms(fn, steps):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        fn()
+        torch.cuda.synchronize()
+        evs[0].record()
+        for i in range(steps):
+            fn()
+            evs[i + 1].record()
+        torch.cuda.synchronize()
+        return evs[0].elapsed_time(evs[-1]) / steps
+
+    ksteps = max(20, min(args.steps, 200))
+    k_ms = {
+        "fmha_fwd_kernel": kernel_ms(lambda: d.fwd(reuse=True), ksteps),
+        "bwd_dq_kernel": kernel_ms(lambda: d.bwd(only="dq"), ksteps),
+        "bwd_dkv_kernel": kernel_ms(lambda: d.bwd(only="dkv"), ksteps),
+    }
+    k_fl = {"fmha_fwd_kernel": fl_fwd, "bwd_dq_kernel": fl_dq, "bwd_dkv_kernel": fl_dkv}
+    dom = max(k_ms, key=k_ms.get)
+    ach = k_fl[dom] / (k_ms[dom] * 1e-3) / 1e12
+    peak = PEAK_TFLOPS[dt]
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": peak,
+                "unit": "TFLOP/s", "frac": round(ach / peak, 4), "traffic": None,
+                "avg_launch_ms": round(k_ms[dom], 5),
+                "kernels_ms": {k: round(v, 5) for k, v in k_ms.items()},
+                "kernels_tflops": {k: round(k_fl[k] / (k_ms[k] * 1e-3) / 1e12, 2) for k in k_ms},
+                "hbm_algorithmic_GBs": round(12.0 * T * H * 64 * 2 / sec / 1e9, 1)}
+
+    out = {
+        "metric": "useful attention TFLOP/s fwd+bwd",
+        "value": round(fl_all / sec / 1e12, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dt, "data": "synthetic",
+        "config": {"workload": b["name"], "baseline_config": args.config, "sequences": int(b["batch"]),
+                   "heads": int(H), "head_dim": 64, "max_seqlen": int(b["max_seqlen"]),
+                   "total_tokens": int(T), "sum_len_sq": sum_l2,
+                   "step": "tile-list build + forward + backward (dQ pass, dK/dV pass)"},
+        "pct_of_mfma_peak": round(100.0 * fl_all / sec / 1e12 / peak, 2),
+        "peak_tflops": peak,
+        "tokens_per_s": round(T / sec, 1),
+        "useful_flop_per_step": fl_all,
+        "roofline": roofline,
+    }
+
+    if not args.no_padded:
+        # the same kernels on the padded layout (every sequence 512 rows, keys past the
+        # true length masked): what a padded framework executes for this batch
+        pd = Dev(wl.pad_batch(b, b["max_seqlen"]))
+        psec = timed(pd.step, max(5, args.steps // 4), max(2, args.warmup // 4))
+        out["padded_baseline"] = {"ms_per_step": round(psec * 1e3, 5),
+                                  "tokens_per_s": round(T / psec, 1),
+                                  "speedup_unpadded_vs_padded": round(psec / sec, 3)}
+        del pd
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        n = b["batch"]
+        if args.config == 5:   # bounded sample: a seeded subset incl. first, last, shortest, longest
+            rng = np.random.default_rng(0)
+            pick = sorted(set([0, n - 1, int(lengths.argmin()), int(lengths.argmax())]
+                              + rng.choice(n, 60, replace=False).tolist()))
+        else:
+            pick = list(range(n))
+        cu = b["cu_seqlens"]
+        rows = np.concatenate([np.arange(cu[i], cu[i + 1]) for i in pick])
+        sub_cu = wl.cu_from_lengths(lengths[pick])
+        x = {nm: wl.bits_to_f64(b[nm][rows], dt) for nm in ("q", "k", "v", "do")}
+        t0 = time.perf_counter()
+        oracle.fwd(x["q"], x["k"], x["v"], sub_cu, b["scale"])
+        oracle.bwd(x["q"], x["k"], x["v"], x["do"], sub_cu, b["scale"])
+        csec = time.perf_counter() - t0
+        sub_fl = 14.0 * float((lengths[pick].astype(np.float64) ** 2).sum()) * H * 64
+        out["cpu_baseline"] = {"value": round(sub_fl / csec / 1e12, 6), "unit": "TFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "%d of %d sequences, all heads, fwd+bwd, %.2f s" % (len(pick), n, csec)}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

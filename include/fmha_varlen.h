@@ -60,16 +60,22 @@ typedef enum { FMHA_F16 = 0, FMHA_BF16 = 1 } fmha_dtype_t;
  * per layer and direction with the same batch, as the paper computes its
  * batch_offset once per mini-batch (Section IV-B-2). */
 #define FMHA_FLAG_REUSE_SCHEDULE 1u
+/* fmha_varlen_bwd only: run one of the two backward passes.  The dQ pass also
+ * writes the row sums of dO o O into the workspace; the dK/dV pass reads them,
+ * so a dK/dV-only call must follow a dQ pass on the same workspace and inputs.
+ * The output pointers of the skipped pass are still validated but not written. */
+#define FMHA_FLAG_BWD_ONLY_DQ 2u
+#define FMHA_FLAG_BWD_ONLY_DKV 4u
 
 typedef struct fmha_varlen_params {
   int32_t batch;        /* number of sequences B >= 0 */
   int32_t total_tokens; /* T = cu_seqlens[B] */
   int32_t heads;        /* H >= 1 */
   int32_t head_dim;     /* must be 64 */
-  int32_t max_seqlen;   /* upper bound on the longest sequence; only sizes the launch.  A longer
-                           sequence is still computed correctly if max_seqlen <= 0 is passed
-                           (no bound assumed); a positive value that is too small is an error
-                           when cu_seqlens_host is given and undefined work loss otherwise */
+  int32_t max_seqlen;   /* upper bound on the longest sequence, or <= 0 if unknown.  It only
+                           sizes the launch (the kernels stride over the tile list, so a
+                           wrong value costs time, not correctness); a value smaller than a
+                           length seen in cu_seqlens_host is reported as an error */
   int32_t dtype;        /* fmha_dtype_t */
   uint32_t flags;       /* FMHA_FLAG_* */
   float scale;          /* multiplies Q K^T; 1/sqrt(64) = 0.125 for Eq. 1 */

@@ -199,6 +199,8 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
                     void* dv, void* stream) {
   int rc = check_common(p, true);
   if (rc) return rc;
+  if ((p->flags & FMHA_FLAG_BWD_ONLY_DQ) && (p->flags & FMHA_FLAG_BWD_ONLY_DKV))
+    return fail(FMHA_ERR_INVALID_ARG, "FMHA_FLAG_BWD_ONLY_DQ and FMHA_FLAG_BWD_ONLY_DKV exclude each other");
   if ((rc = check_ptr("q", q)) || (rc = check_ptr("k", k)) || (rc = check_ptr("v", v)) ||
       (rc = check_ptr("o", o)) || (rc = check_ptr("d_o", d_o)) || (rc = check_ptr("lse", lse)) ||
       (rc = check_ptr("dq", dq)) || (rc = check_ptr("dk", dk)) || (rc = check_ptr("dv", dv)))
@@ -231,12 +233,14 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   a.dk = static_cast<uint16_t*>(dk);
   a.dv = static_cast<uint16_t*>(dv);
   const unsigned grid = grid_for(p);
+  const bool run_dq = !(p->flags & FMHA_FLAG_BWD_ONLY_DKV);
+  const bool run_dkv = !(p->flags & FMHA_FLAG_BWD_ONLY_DQ);
   if (p->dtype == FMHA_F16) {
-    fmha::bwd_dq_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
-    fmha::bwd_dkv_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
+    if (run_dq) fmha::bwd_dq_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
+    if (run_dkv) fmha::bwd_dkv_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
   } else {
-    fmha::bwd_dq_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
-    fmha::bwd_dkv_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
+    if (run_dq) fmha::bwd_dq_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
+    if (run_dkv) fmha::bwd_dkv_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FMHA_ERR_HIP, "backward launch failed: %s", hipGetErrorString(e));

@@ -17,6 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libfmha_varlen.so")
 FMHA_OK, FMHA_ERR_INVALID_ARG, FMHA_ERR_UNSUPPORTED, FMHA_ERR_WORKSPACE, FMHA_ERR_HIP = range(5)
 FMHA_F16, FMHA_BF16 = 0, 1
 FMHA_FLAG_REUSE_SCHEDULE = 1
+FMHA_FLAG_BWD_ONLY_DQ = 2
+FMHA_FLAG_BWD_ONLY_DKV = 4
 
 EXPORTS = ("fmha_varlen_workspace_size", "fmha_varlen_fwd", "fmha_varlen_bwd",
            "fmha_varlen_schedule_info", "fmha_last_error")
@@ -109,13 +111,14 @@ def alloc_workspace(batch: int, total_tokens: int, heads: int, need_bwd: bool, d
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host, reuse_schedule):
+def _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host, reuse_schedule,
+            extra_flags=0):
     p = Params()
     p.batch = cu_seqlens.numel() - 1
     p.total_tokens, p.heads, p.head_dim = q.shape
     p.max_seqlen = int(max_seqlen)
     p.dtype = _dtype_code(q)
-    p.flags = FMHA_FLAG_REUSE_SCHEDULE if reuse_schedule else 0
+    p.flags = (FMHA_FLAG_REUSE_SCHEDULE if reuse_schedule else 0) | extra_flags
     p.scale = float(scale)
     assert cu_seqlens.dtype == torch.int32 and cu_seqlens.is_cuda and cu_seqlens.is_contiguous()
     p.cu_seqlens = cu_seqlens.data_ptr()
@@ -148,9 +151,12 @@ def fmha_varlen_fwd(q, k, v, cu_seqlens, max_seqlen, scale, o, lse, workspace, *
 
 
 def fmha_varlen_bwd(q, k, v, o, d_o, lse, cu_seqlens, max_seqlen, scale, dq, dk, dv, workspace, *,
-                    seqused=None, cu_seqlens_host=None, reuse_schedule=False):
-    """Enqueue the backward pass on torch's current stream; fills dq, dk, dv."""
-    p, keep = _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host, reuse_schedule)
+                    seqused=None, cu_seqlens_host=None, reuse_schedule=False, only=None):
+    """Enqueue the backward pass on torch's current stream; fills dq, dk, dv.
+    `only` = "dq" or "dkv" runs one of the two passes (see the header)."""
+    extra = {None: 0, "dq": FMHA_FLAG_BWD_ONLY_DQ, "dkv": FMHA_FLAG_BWD_ONLY_DKV}[only]
+    p, keep = _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host,
+                      reuse_schedule, extra)
     p.q_stride, p.k_stride, p.v_stride, p.o_stride = map(_tok_stride, (q, k, v, o))
     p.do_stride, p.dq_stride, p.dk_stride, p.dv_stride = map(_tok_stride, (d_o, dq, dk, dv))
     _check(lib().fmha_varlen_bwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
