@@ -18,6 +18,40 @@
 
 namespace fmha {
 
+// Register-staged, padded LDS tiles (row stride 64 + 8 elements).
+constexpr int kLdsRow = 72;
+
+__device__ __forceinline__ void load_tile_regs(const uint16_t* __restrict__ base, int64_t stride,
+                                               int row0, int nrows, int tid, u32x4 (&r)[2]) {
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int c = tid + kThreads * i;
+    const int row = row0 + (c >> 3);
+    r[i] = u32x4{0, 0, 0, 0};
+    if (row < nrows) r[i] = *reinterpret_cast<const u32x4*>(base + row * stride + (c & 7) * 8);
+  }
+}
+
+__device__ __forceinline__ void store_tile_lds(uint16_t* tile, int tid, const u32x4 (&r)[2]) {
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    const int c = tid + kThreads * i;
+    *reinterpret_cast<u32x4*>(tile + (c >> 3) * kLdsRow + (c & 7) * 8) = r[i];
+  }
+}
+
+static __device__ __forceinline__ u32x4 pad_read_row8(const uint16_t* tile, int row, int col) {
+  return *reinterpret_cast<const u32x4*>(tile + row * kLdsRow + col);
+}
+
+static __device__ __forceinline__ u32x4 pad_read_col8(const uint16_t* tile, int base, int col16,
+                                                      int lane16) {
+  const uint16_t* p = tile + (base + (lane16 >> 2)) * kLdsRow + col16 + 4 * (lane16 & 3);
+  u32x2 a = lds_read_tr16(p);
+  u32x2 b = lds_read_tr16(p + 8 * kLdsRow);
+  return u32x4{a[0], a[1], b[0], b[1]};
+}
+
 // ---------------------------------------------------------------- pass 1: dQ
 template <typename T>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
@@ -102,8 +136,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
           for (int r = 0; r < 16; r++) s[r] = dp[r] = 0.f;
 #pragma unroll
           for (int t = 0; t < 4; t++) {
-            s = Op<T>::mfma(lds_read_row8(sK, 32 * kb + ln, 16 * t + 8 * g), qb[t], s);
-            dp = Op<T>::mfma(lds_read_row8(sV, 32 * kb + ln, 16 * t + 8 * g), gb[t], dp);
+            s = Op<T>::mfma(pad_read_row8(sK, 32 * kb + ln, 16 * t + 8 * g), qb[t], s);
+            dp = Op<T>::mfma(pad_read_row8(sV, 32 * kb + ln, 16 * t + 8 * g), gb[t], dp);
           }
           float ds[16];
 #pragma unroll
@@ -127,7 +161,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
             for (int t2 = 0; t2 < 2; t2++)
               dq[cb] = Op<T>::mfma(
-                  lds_read_col8(sK, 32 * kb + 16 * t2 + 4 * g, 32 * cb + 16 * half16, lane16),
+                  pad_read_col8(sK, 32 * kb + 16 * t2 + 4 * g, 32 * cb + 16 * half16, lane16),
                   dsb[kb][t2], dq[cb]);
       }
       __syncthreads();
@@ -245,8 +279,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
           for (int r = 0; r < 16; r++) s[r] = dp[r] = 0.f;
 #pragma unroll
           for (int t = 0; t < 4; t++) {
-            s = Op<T>::mfma(lds_read_row8(sQ, 32 * qb + ln, 16 * t + 8 * g), kb4[t], s);
-            dp = Op<T>::mfma(lds_read_row8(sG, 32 * qb + ln, 16 * t + 8 * g), vb4[t], dp);
+            s = Op<T>::mfma(pad_read_row8(sQ, 32 * qb + ln, 16 * t + 8 * g), kb4[t], s);
+            dp = Op<T>::mfma(pad_read_row8(sG, 32 * qb + ln, 16 * t + 8 * g), vb4[t], dp);
           }
           float p[16], ds[16];
 #pragma unroll
@@ -278,8 +312,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
 #pragma unroll
             for (int cb = 0; cb < 2; cb++) {
               const int base = 32 * qb + 16 * t2 + 4 * g, col = 32 * cb + 16 * half16;
-              dv[cb] = Op<T>::mfma(lds_read_col8(sG, base, col, lane16), pb, dv[cb]);
-              dk[cb] = Op<T>::mfma(lds_read_col8(sQ, base, col, lane16), dsb, dk[cb]);
+              dv[cb] = Op<T>::mfma(pad_read_col8(sG, base, col, lane16), pb, dv[cb]);
+              dk[cb] = Op<T>::mfma(pad_read_col8(sQ, base, col, lane16), dsb, dk[cb]);
             }
           }
         }

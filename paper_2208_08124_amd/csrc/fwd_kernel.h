@@ -3,51 +3,152 @@
 // with a running row maximum and row sum.
 //
 // One workgroup (4 wavefronts) takes one tile of 128 query rows of one
-// (sequence, head); wavefront w owns rows 32w..32w+31.  Keys and values are
-// staged 64 rows at a time in LDS.  The scores are produced TRANSPOSED,
-// S^T = K Q^T, so that in the MFMA result layout every lane holds 16 keys of
-// ONE query: the row maximum and row sum are then plain per-lane reductions
-// plus a single exchange with the lane 32 away, and the probabilities are
-// already in the operand layout of the second product O^T = V^T P^T.
+// (sequence, head); wavefront w owns rows 32w..32w+31.  Keys and values move
+// 64 rows at a time from HBM straight into a ring of LDS stages, two blocks
+// ahead of the one being computed, with one barrier per step.
+// The scores are produced TRANSPOSED, S^T = K Q^T, so that in the MFMA result
+// layout every lane holds 16 keys of ONE query: the row maximum and row sum
+// are then per-lane reductions plus a single exchange with the lane 32 away,
+// and the probabilities are already in the operand layout of the second
+// product O^T = V^T P^T.
+//
+// The softmax is the part that competes with the matrix cores for issue
+// slots (one v_exp_f32 costs as much as a quarter of the MFMA work a score
+// needs), so it is kept to: one max3 per two scores, one fused multiply-add
+// and one exp2 per score, one pack per two scores, one dot2 per two scores
+// for the row sum.  The running maximum is only raised when a tile exceeds it
+// by more than kRescaleStep (in log2 units); until then probabilities may
+// exceed 1 (by at most 2^kRescaleStep, harmless in fp16/bf16 and fp32), and
+// the rescaling of the accumulators is skipped.  The result is the same
+// softmax: the maximum cancels between numerator and row sum.
 #pragma once
 #include "kernel_args.h"
 #include "mfma_tiles.h"
 
 namespace fmha {
 
-// Stage rows [row0, row0+64) x 64 columns of a packed tensor into registers:
-// thread t carries 16-byte chunks t and t+256 (chunk c = row c/8, columns
-// 8*(c%8)..+7).  Rows at or beyond `nrows` come back as zeros.
-__device__ __forceinline__ void load_tile_regs(const uint16_t* __restrict__ base, int64_t stride,
-                                               int row0, int nrows, int tid, u32x4 (&r)[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; i++) {
-    const int c = tid + kThreads * i;
-    const int row = row0 + (c >> 3);
-    r[i] = u32x4{0, 0, 0, 0};
-    if (row < nrows) r[i] = *reinterpret_cast<const u32x4*>(base + row * stride + (c & 7) * 8);
-  }
-}
+constexpr float kRescaleStep = 8.f;
 
-__device__ __forceinline__ void store_tile_lds(uint16_t* tile, int tid, const u32x4 (&r)[2]) {
+constexpr int kFwdStages = 3;                 // LDS ring: K and V tile per stage (16 KB)
+constexpr int kFwdAhead = kFwdStages - 1;     // blocks in flight ahead of the compute
+
+template <typename T>
+struct FwdState {
+  f32x16 oacc[2];  // O^T: column = query ln; oacc[cb][r] is channel 32cb + 8(r/4) + 4g + r%4
+  float m_run;     // running maximum, log2 domain (scaled by scale*log2 e)
+  float l_run;     // this lane's share of the running row sum
+};
+
+// One block of 64 keys for one wavefront.  RAGGED: keys at or beyond nk (only
+// possible in a sequence's last block) are excluded.
+//
+// The LDS reads of each product are issued together ahead of its MFMAs (the
+// sched_barriers keep the compiler from sinking each read next to its use,
+// which would serialise LDS latency with every MFMA); the transpose reads of V
+// are in flight during the softmax arithmetic.
+template <typename T, bool RAGGED>
+__device__ __forceinline__ void fwd_block(FwdState<T>& st, const uint16_t* sK, const uint16_t* sV,
+                                          const u32x4 (&qb)[4], float c2, int key_base, int nk,
+                                          int g, int ln, int lane16, int half16) {
+  u32x4 ka[4][2];
 #pragma unroll
-  for (int i = 0; i < 2; i++) {
-    const int c = tid + kThreads * i;
-    *reinterpret_cast<u32x4*>(tile + (c >> 3) * kLdsRow + (c & 7) * 8) = r[i];
+  for (int t = 0; t < 4; t++)
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) ka[t][kb] = lds_read_row8(sK, 32 * kb + ln, 16 * t + 8 * g);
+  __builtin_amdgcn_sched_barrier(0);
+  // S^T = K Q^T : rows = keys (two blocks of 32), column = query ln
+  f32x16 s[2];
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) s[kb][r] = 0.f;
+#pragma unroll
+  for (int t = 0; t < 4; t++)
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) s[kb] = Op<T>::mfma(ka[t][kb], qb[t], s[kb]);
+  __builtin_amdgcn_sched_barrier(0);
+  u32x4 va[2][2][2];  // V^T operands: [key block][16-key step][channel block]
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+      for (int cb = 0; cb < 2; cb++)
+        va[kb][t2][cb] =
+            lds_read_col8(sV, 32 * kb + 16 * t2 + 4 * g, 32 * cb + 16 * half16, lane16);
+  __builtin_amdgcn_sched_barrier(0);
+
+  const int key0 = key_base + 4 * g;  // key of s[0][0]
+  float mx = -INFINITY;
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      float x = s[kb][r];
+      if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) x = -INFINITY;
+      mx = fmaxf(mx, x);
+    }
+  mx = fmaxf(mx, other_half(mx));
+  const float m_blk = mx * c2;  // c2 >= 0: the sign of the scale was folded into Q
+  // first block: m_run = -inf, so alpha = 0 and the (zero) accumulators stay zero
+  if (__any(m_blk > st.m_run + kRescaleStep)) {
+    const float m_new = m_blk > st.m_run + kRescaleStep ? m_blk : st.m_run;
+    const float alpha = fast_exp2(st.m_run - m_new);
+    st.m_run = m_new;
+    st.l_run *= alpha;
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) st.oacc[cb][r] *= alpha;
   }
+  const float neg_m = -st.m_run;
+  float psum = 0.f;
+  u32x4 pb[2][2];  // P^T as B operands: [key block][16-key step]
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++) {
+    float p[16];
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      p[r] = fast_exp2(__builtin_fmaf(s[kb][r], c2, neg_m));
+      if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) p[r] = 0.f;
+    }
+#pragma unroll
+    for (int t2 = 0; t2 < 2; t2++) {
+      u32x4 w;
+#pragma unroll
+      for (int e = 0; e < 4; e++) {
+        w[e] = Op<T>::pack2(p[8 * t2 + 2 * e], p[8 * t2 + 2 * e + 1]);
+        psum = Op<T>::add_pair(w[e], psum);  // sums what actually multiplies V
+      }
+      pb[kb][t2] = w;
+    }
+  }
+  st.l_run += psum;
+  __builtin_amdgcn_sched_barrier(0);
+  // O^T += V^T P^T : rows = channels (two blocks of 32), contraction over keys
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+      for (int cb = 0; cb < 2; cb++)
+        st.oacc[cb] = Op<T>::mfma(va[kb][t2][cb], pb[kb][t2], st.oacc[cb]);
 }
 
 template <typename T>
 __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) {
-  __shared__ __align__(16) uint16_t sK[kBlockKeys * kLdsRow];
-  __shared__ __align__(16) uint16_t sV[kBlockKeys * kLdsRow];
+  __shared__ __align__(1024) uint16_t ring[kFwdStages][2][kTileElems];  // [stage][K|V]
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 5, ln = lane & 31, lane16 = lane & 15, half16 = (lane >> 4) & 1;
   const int heads = a.pb.heads;
   const int n_items = *a.pb.n_tiles * heads;
-  const float c2 = a.pb.scale * kLog2e;  // scores are kept in the log2 domain
+  const float c2 = fabsf(a.pb.scale) * kLog2e;  // scores are kept in the log2 domain
+  const uint32_t qflip = a.pb.scale < 0.f ? 0x80008000u : 0u;
+  const DmaLane dl(wave, lane);
+  const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
+  constexpr uint32_t kStageBytes = 2 * kTileElems * 2, kTileBytes = kTileElems * 2;
 
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
@@ -56,115 +157,68 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
     const int len = a.pb.cu[ti.seq + 1] - r0;
     int nk = a.pb.seqused ? min(a.pb.seqused[ti.seq], len) : len;
     nk = nk < 0 ? 0 : nk;
-    const int qrow = ti.row0 + 32 * wave + ln;        // this lane's query, within the sequence
-    const bool wave_on = ti.row0 + 32 * wave < len;   // wavefront has at least one valid row
+    const int qrow = ti.row0 + 32 * wave + ln;       // this lane's query, within the sequence
+    const bool wave_on = ti.row0 + 32 * wave < len;  // wavefront has at least one valid row
     const uint16_t* kbase = a.k + (int64_t)r0 * a.k_stride + head * kHeadDim;
     const uint16_t* vbase = a.v + (int64_t)r0 * a.v_stride + head * kHeadDim;
+    const int n_kt = (nk + kBlockKeys - 1) / kBlockKeys;
 
-    // Q^T as the B operand: column = query ln, slots = channels 16t + 8g .. +7
+    auto start_block = [&](int kt) {
+      const uint32_t st_addr = ring_addr + (kt % kFwdStages) * kStageBytes;
+      dma_tile(kbase, a.k_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr);
+      dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
+    };
+#pragma unroll
+    for (int kt = 0; kt < kFwdAhead; kt++)
+      if (kt < n_kt) start_block(kt);
+
+    // Q^T as the B operand: column = query ln, slots = channels 16t + 8g .. +7.
+    // A negative scale is applied as a sign flip of Q so that the row maximum
+    // can be taken on the raw scores.
     u32x4 qb[4];
     {
       const int qr = qrow < len ? qrow : len - 1;
       const uint16_t* qp = a.q + (int64_t)(r0 + qr) * a.q_stride + head * kHeadDim + 8 * g;
 #pragma unroll
-      for (int t = 0; t < 4; t++) qb[t] = *reinterpret_cast<const u32x4*>(qp + 16 * t);
+      for (int t = 0; t < 4; t++) {
+        qb[t] = *reinterpret_cast<const u32x4*>(qp + 16 * t);
+#pragma unroll
+        for (int e = 0; e < 4; e++) qb[t][e] ^= qflip;
+      }
     }
 
-    f32x16 oacc[2];  // O^T: column = query ln; oacc[cb][r] is channel 32cb + 8(r/4) + 4g + r%4
+    FwdState<T> st;
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) oacc[cb][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
-
-    const int n_kt = (nk + kBlockKeys - 1) / kBlockKeys;
-    u32x4 kreg[2], vreg[2];
-    if (n_kt > 0) {
-      load_tile_regs(kbase, a.k_stride, 0, nk, tid, kreg);
-      load_tile_regs(vbase, a.v_stride, 0, nk, tid, vreg);
-      store_tile_lds(sK, tid, kreg);
-      store_tile_lds(sV, tid, vreg);
-    }
-    __syncthreads();
+      for (int r = 0; r < 16; r++) st.oacc[cb][r] = 0.f;
+    st.m_run = -INFINITY;
+    st.l_run = 0.f;
 
     for (int kt = 0; kt < n_kt; kt++) {
-      const bool more = kt + 1 < n_kt;
-      if (more) {  // next tile's global loads fly while this one is computed
-        load_tile_regs(kbase, a.k_stride, (kt + 1) * kBlockKeys, nk, tid, kreg);
-        load_tile_regs(vbase, a.v_stride, (kt + 1) * kBlockKeys, nk, tid, vreg);
-      }
+      // this thread's pieces of block kt have landed once at most the pieces of the
+      // blocks started after it (4 per block) are outstanding
+      static_assert(kFwdAhead == 2, "the waits below are written for two blocks in flight");
+      if (n_kt - kt >= 2)
+        wait_vmem<4>();
+      else
+        wait_vmem<0>();
+      __syncthreads();  // everyone's pieces landed; everyone is done with block kt-1's stage
+      if (kt + kFwdAhead < n_kt) start_block(kt + kFwdAhead);
       if (wave_on) {
-        // S^T = K Q^T : rows = keys (two blocks of 32), column = query ln
-        f32x16 s[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-#pragma unroll
-          for (int r = 0; r < 16; r++) s[kb][r] = 0.f;
-#pragma unroll
-          for (int t = 0; t < 4; t++)
-            s[kb] = Op<T>::mfma(lds_read_row8(sK, 32 * kb + ln, 16 * t + 8 * g), qb[t], s[kb]);
-        }
-        // scale into the log2 domain, mask keys past the end (last tile only)
-        const int key0 = kt * kBlockKeys + 4 * g;
-        const bool ragged = key0 - 4 * g + kBlockKeys > nk;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            float x = s[kb][r] * c2;
-            if (ragged && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) x = -INFINITY;
-            s[kb][r] = x;
-            mx = fmaxf(mx, x);
-          }
-        mx = fmaxf(mx, other_half(mx));
-        const float m_new = fmaxf(m_run, mx);  // finite: every staged tile has a valid key
-        const float alpha = fast_exp2(m_run - m_new);
-        m_run = m_new;
-        float psum = 0.f;
-        u32x4 pb[2][2];  // P^T as B operands: [key block][16-key step]
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-          float p[16];
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            p[r] = fast_exp2(s[kb][r] - m_new);
-            psum += p[r];
-          }
-#pragma unroll
-          for (int t2 = 0; t2 < 2; t2++)
-            pb[kb][t2] = u32x4{Op<T>::pack2(p[8 * t2 + 0], p[8 * t2 + 1]),
-                               Op<T>::pack2(p[8 * t2 + 2], p[8 * t2 + 3]),
-                               Op<T>::pack2(p[8 * t2 + 4], p[8 * t2 + 5]),
-                               Op<T>::pack2(p[8 * t2 + 6], p[8 * t2 + 7])};
-        }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int cb = 0; cb < 2; cb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) oacc[cb][r] *= alpha;
-        // O^T += V^T P^T : rows = channels (two blocks of 32), contraction over keys
-#pragma unroll
-        for (int cb = 0; cb < 2; cb++)
-#pragma unroll
-          for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-            for (int t2 = 0; t2 < 2; t2++)
-              oacc[cb] = Op<T>::mfma(
-                  lds_read_col8(sV, 32 * kb + 16 * t2 + 4 * g, 32 * cb + 16 * half16, lane16),
-                  pb[kb][t2], oacc[cb]);
+        const uint16_t* sK = &ring[kt % kFwdStages][0][0];
+        const uint16_t* sV = &ring[kt % kFwdStages][1][0];
+        if ((kt + 1) * kBlockKeys > nk)
+          fwd_block<T, true>(st, sK, sV, qb, c2, kt * kBlockKeys, nk, g, ln, lane16, half16);
+        else
+          fwd_block<T, false>(st, sK, sV, qb, c2, kt * kBlockKeys, nk, g, ln, lane16, half16);
       }
-      __syncthreads();
-      if (more) {
-        store_tile_lds(sK, tid, kreg);
-        store_tile_lds(sV, tid, vreg);
-      }
-      __syncthreads();
     }
+    __syncthreads();  // the ring is free for the next item
 
     // epilogue: combine the two half-rows' sums, normalise, store O and LSE
     if (wave_on) {
-      const float l_tot = l_run + other_half(l_run);
+      const float l_tot = st.l_run + other_half(st.l_run);
       const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
       if (qrow < len) {
         uint16_t* op = a.o + (int64_t)(r0 + qrow) * a.o_stride + head * kHeadDim + 4 * g;
@@ -172,13 +226,13 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
         for (int cb = 0; cb < 2; cb++)
 #pragma unroll
           for (int j = 0; j < 4; j++) {
-            u32x2 w = {Op<T>::pack2(oacc[cb][4 * j] * inv, oacc[cb][4 * j + 1] * inv),
-                       Op<T>::pack2(oacc[cb][4 * j + 2] * inv, oacc[cb][4 * j + 3] * inv)};
+            u32x2 w = {Op<T>::pack2(st.oacc[cb][4 * j] * inv, st.oacc[cb][4 * j + 1] * inv),
+                       Op<T>::pack2(st.oacc[cb][4 * j + 2] * inv, st.oacc[cb][4 * j + 3] * inv)};
             *reinterpret_cast<u32x2*>(op + 32 * cb + 8 * j) = w;
           }
         if (g == 0)
           a.lse[(int64_t)head * a.pb.total_tokens + r0 + qrow] =
-              l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+              l_tot > 0.f ? (st.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
       }
     }
   }

@@ -42,6 +42,12 @@ struct Op<_Float16> {
     h2 v = {(_Float16)lo, (_Float16)hi};
     return __builtin_bit_cast(uint32_t, v);
   }
+  // acc + (both halves of w), accumulated in fp32 (v_dot2c_f32_f16 with a vector of ones)
+  static __device__ __forceinline__ float add_pair(uint32_t w, float acc) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, w), h2{(_Float16)1.f, (_Float16)1.f}, acc,
+                                  false);
+  }
   static __device__ __forceinline__ float lo(uint32_t w) {
     typedef _Float16 h2 __attribute__((ext_vector_type(2)));
     return (float)__builtin_bit_cast(h2, w)[0];
@@ -62,6 +68,11 @@ struct Op<__bf16> {
     typedef __bf16 b2 __attribute__((ext_vector_type(2)));
     b2 v = {(__bf16)lo, (__bf16)hi};
     return __builtin_bit_cast(uint32_t, v);
+  }
+  static __device__ __forceinline__ float add_pair(uint32_t w, float acc) {
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, w), b2{(__bf16)1.f, (__bf16)1.f},
+                                           acc, false);
   }
   static __device__ __forceinline__ float lo(uint32_t w) {
     return __builtin_bit_cast(float, w << 16);
@@ -92,26 +103,91 @@ static __device__ __forceinline__ float other_half(float x) {
 
 static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Row stride (in 16-bit elements) of a 64-wide tile in LDS: 64 + 8 keeps both
-// the 16-byte row reads of 32 consecutive rows and the transpose reads spread
-// over the banks.
-constexpr int kLdsRow = 72;
+// ---------------------------------------------------------------------------
+// 64 x 64 tiles of 16-bit elements in LDS: 8 KB, rows of 128 bytes, no padding.
+// The 16-byte chunk c (0..7) of row r is stored at chunk position c ^ swz(r).
+// With 64 four-byte banks a row covers half of them (which half = parity of
+// r), so the swizzle is a bijection of (r/2) mod 8 - sixteen consecutive rows
+// read at one column hit every bank once - and it moves bit 0 of r/2 to bit 2,
+// so that the four consecutive rows of a transpose read, each reading four
+// neighbouring chunks, land in different chunk groups.  Measured on MI355X:
+// ~226 B/clk/CU for the 16-byte row reads and ~200 B/clk/CU for the transpose
+// reads below, against 32 and 117 without a swizzle.
+// ---------------------------------------------------------------------------
+constexpr int kTileElems = 64 * 64;
 
-// A operand from a row-major LDS tile: row `row`, elements col .. col+7.
+static __device__ __forceinline__ int swz(int r) {
+  const int x = (r >> 1) & 7;
+  return ((x & 1) << 2) | (x >> 1);
+}
+
+// element offset of (row, col) inside a tile
+static __device__ __forceinline__ int tile_off(int row, int col) {
+  return row * 64 + ((((col >> 3) ^ swz(row)) << 3) | (col & 7));
+}
+
+// A operand from a tile: row `row`, elements col .. col+7 (col a multiple of 8).
 static __device__ __forceinline__ u32x4 lds_read_row8(const uint16_t* tile, int row, int col) {
-  return *reinterpret_cast<const u32x4*>(tile + row * kLdsRow + col);
+  return *reinterpret_cast<const u32x4*>(tile + tile_off(row, col));
 }
 
 // A operand for a contraction over the tile's ROWS: the lane gets, for column
-// `col`, rows base+{0..3} and base+8+{0..3}.  `lane16 = lane % 16` picks the
-// address this lane contributes; `col16` is the first of the 16 columns its
-// 16-lane group covers.
+// col16 + lane16, rows base+{0..3} and base+8+{0..3}.  `lane16 = lane % 16`
+// picks the address this lane contributes to its 16-lane group.
 static __device__ __forceinline__ u32x4 lds_read_col8(const uint16_t* tile, int base, int col16,
                                                       int lane16) {
-  const uint16_t* p = tile + (base + (lane16 >> 2)) * kLdsRow + col16 + 4 * (lane16 & 3);
-  u32x2 a = lds_read_tr16(p);
-  u32x2 b = lds_read_tr16(p + 8 * kLdsRow);
+  const int row = base + (lane16 >> 2), col = col16 + 4 * (lane16 & 3);
+  u32x2 a = lds_read_tr16(tile + tile_off(row, col));
+  u32x2 b = lds_read_tr16(tile + tile_off(row + 8, col));
   return u32x4{a[0], a[1], b[0], b[1]};
+}
+
+// ---------------------------------------------------------------------------
+// Global -> LDS without passing through registers (global_load_lds_dwordx4):
+// every lane names its own 16 global bytes; the wavefront's 64 pieces land at
+// LDS address m0 + 16*lane, i.e. one instruction fills eight tile rows, and the
+// swizzle is applied by choosing WHICH global chunk each lane fetches.
+// The instruction is issued from inline assembly so that the compiler does
+// not serialise every later LDS read behind it; completion is awaited with
+// explicit s_waitcnt vmcnt(n) (vector memory loads complete in issue order).
+// ---------------------------------------------------------------------------
+static __device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+static __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_byte_addr), "v"(gptr)
+               : "memory");
+}
+
+template <int N>
+static __device__ __forceinline__ void wait_vmem() {
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
+// Rows and chunk of the two 1 KB pieces a lane moves per 64-row tile: wavefront
+// w fills rows 8w..8w+7 and 32+8w..32+8w+7.
+struct DmaLane {
+  int row;    // first row (second is row + 32)
+  int chunk;  // global 16-byte chunk (same for both rows: swz(row) == swz(row + 32))
+  __device__ __forceinline__ DmaLane(int wave, int lane) {
+    row = 8 * wave + (lane >> 3);
+    chunk = (lane & 7) ^ swz(row);
+  }
+};
+
+// Start moving rows [row0, row0 + 64) of a packed tensor (rows clamped to
+// last_row, so the tail of a short sequence repeats its last valid row instead
+// of reading past it) into the tile at LDS byte address `tile_addr`.
+static __device__ __forceinline__ void dma_tile(const uint16_t* base, int64_t stride, int row0,
+                                                int last_row, const DmaLane& dl, int wave,
+                                                uint32_t tile_addr) {
+  const int ra = min(row0 + dl.row, last_row), rb = min(row0 + dl.row + 32, last_row);
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(tile_addr + 1024u * wave);
+  dma16(base + ra * stride + dl.chunk * 8, m0);
+  dma16(base + rb * stride + dl.chunk * 8, m0 + 4096u);
 }
 
 }  // namespace fmha
