@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, help="workload 2..5 (3 = headline)")
+    ap.add_argument("--uniform", type=str, default=None, metavar="L,B",
+                    help="kernel study: B sequences of exactly L tokens instead of --config's lengths")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
     return ap.parse_args()
@@ -56,6 +58,11 @@ def main():
     dev_dt = {"f16": torch.float16, "bf16": torch.bfloat16}
 
     b = wl.make_workload(args.config, backward=True)
+    if args.uniform:
+        ul, ub = (int(x) for x in args.uniform.split(","))
+        w = wl.WORKLOADS[args.config]
+        b = wl.make_batch([ul] * ub, w.heads, w.dtype, w.seed, backward=True)
+        b["name"] = "uniform_%dx%d" % (ul, ub)
     dt = b["dtype"]
     lengths = b["lengths"]
     T, H = b["total_tokens"], b["heads"]

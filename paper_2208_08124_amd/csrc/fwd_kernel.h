@@ -49,12 +49,12 @@ struct FwdState {
 template <typename T, bool RAGGED>
 __device__ __forceinline__ void fwd_block(FwdState<T>& st, const uint16_t* sK, const uint16_t* sV,
                                           const u32x4 (&qb)[4], float c2, int key_base, int nk,
-                                          int g, int ln, int lane16, int half16) {
+                                          int g, const RowRead& rr, const ColRead& cr) {
   u32x4 ka[4][2];
 #pragma unroll
   for (int t = 0; t < 4; t++)
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++) ka[t][kb] = lds_read_row8(sK, 32 * kb + ln, 16 * t + 8 * g);
+    for (int kb = 0; kb < 2; kb++) ka[t][kb] = rr.read(sK, kb, t);
   __builtin_amdgcn_sched_barrier(0);
   // S^T = K Q^T : rows = keys (two blocks of 32), column = query ln
   f32x16 s[2];
@@ -74,20 +74,20 @@ __device__ __forceinline__ void fwd_block(FwdState<T>& st, const uint16_t* sK, c
     for (int t2 = 0; t2 < 2; t2++)
 #pragma unroll
       for (int cb = 0; cb < 2; cb++)
-        va[kb][t2][cb] =
-            lds_read_col8(sV, 32 * kb + 16 * t2 + 4 * g, 32 * cb + 16 * half16, lane16);
+        va[kb][t2][cb] = cr.read(sV, 2 * kb + t2, cb);
   __builtin_amdgcn_sched_barrier(0);
 
   const int key0 = key_base + 4 * g;  // key of s[0][0]
-  float mx = -INFINITY;
+  float mxs[2] = {-INFINITY, -INFINITY};  // two independent chains
 #pragma unroll
   for (int kb = 0; kb < 2; kb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       float x = s[kb][r];
       if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) x = -INFINITY;
-      mx = fmaxf(mx, x);
+      mxs[kb] = fmaxf(mxs[kb], x);
     }
+  float mx = fmaxf(mxs[0], mxs[1]);
   mx = fmaxf(mx, other_half(mx));
   const float m_blk = mx * c2;  // c2 >= 0: the sign of the scale was folded into Q
   // first block: m_run = -inf, so alpha = 0 and the (zero) accumulators stay zero
@@ -141,12 +141,14 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
-  const int g = lane >> 5, ln = lane & 31, lane16 = lane & 15, half16 = (lane >> 4) & 1;
+  const int g = lane >> 5, ln = lane & 31;
   const int heads = a.pb.heads;
   const int n_items = *a.pb.n_tiles * heads;
   const float c2 = fabsf(a.pb.scale) * kLog2e;  // scores are kept in the log2 domain
   const uint32_t qflip = a.pb.scale < 0.f ? 0x80008000u : 0u;
   const DmaLane dl(wave, lane);
+  const RowRead rr(ln, g);
+  const ColRead cr(lane);
   const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
   constexpr uint32_t kStageBytes = 2 * kTileElems * 2, kTileBytes = kTileElems * 2;
 
@@ -163,14 +165,24 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
     const uint16_t* vbase = a.v + (int64_t)r0 * a.v_stride + head * kHeadDim;
     const int n_kt = (nk + kBlockKeys - 1) / kBlockKeys;
 
-    auto start_block = [&](int kt) {
-      const uint32_t st_addr = ring_addr + (kt % kFwdStages) * kStageBytes;
-      dma_tile(kbase, a.k_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr);
-      dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
+    // this lane's chunk in its two rows of block 0
+    const uint16_t* kpa = kbase + dl.row * a.k_stride + dl.chunk * 8;
+    const uint16_t* vpa = vbase + dl.row * a.v_stride + dl.chunk * 8;
+    auto start_block = [&](int kt, int stage) {
+      const uint32_t st_addr = ring_addr + stage * kStageBytes;
+      if ((kt + 1) * kBlockKeys <= nk) {
+        const uint16_t* ka_ = kpa + (int64_t)kt * kBlockKeys * a.k_stride;
+        const uint16_t* va_ = vpa + (int64_t)kt * kBlockKeys * a.v_stride;
+        dma_tile_full(ka_, ka_ + 32 * a.k_stride, wave, st_addr);
+        dma_tile_full(va_, va_ + 32 * a.v_stride, wave, st_addr + kTileBytes);
+      } else {
+        dma_tile(kbase, a.k_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr);
+        dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
+      }
     };
 #pragma unroll
     for (int kt = 0; kt < kFwdAhead; kt++)
-      if (kt < n_kt) start_block(kt);
+      if (kt < n_kt) start_block(kt, kt);
 
     // Q^T as the B operand: column = query ln, slots = channels 16t + 8g .. +7.
     // A negative scale is applied as a sign flip of Q so that the row maximum
@@ -195,6 +207,7 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
     st.m_run = -INFINITY;
     st.l_run = 0.f;
 
+    int stage = 0;  // kt % kFwdStages
     for (int kt = 0; kt < n_kt; kt++) {
       // this thread's pieces of block kt have landed once at most the pieces of the
       // blocks started after it (4 per block) are outstanding
@@ -204,15 +217,17 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
       else
         wait_vmem<0>();
       __syncthreads();  // everyone's pieces landed; everyone is done with block kt-1's stage
-      if (kt + kFwdAhead < n_kt) start_block(kt + kFwdAhead);
+      const int ahead = stage == 0 ? kFwdStages - 1 : stage - 1;  // (kt + kFwdAhead) % kFwdStages
+      if (kt + kFwdAhead < n_kt) start_block(kt + kFwdAhead, ahead);
       if (wave_on) {
-        const uint16_t* sK = &ring[kt % kFwdStages][0][0];
-        const uint16_t* sV = &ring[kt % kFwdStages][1][0];
+        const uint16_t* sK = &ring[0][0][0] + stage * (2 * kTileElems);
+        const uint16_t* sV = sK + kTileElems;
         if ((kt + 1) * kBlockKeys > nk)
-          fwd_block<T, true>(st, sK, sV, qb, c2, kt * kBlockKeys, nk, g, ln, lane16, half16);
+          fwd_block<T, true>(st, sK, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
         else
-          fwd_block<T, false>(st, sK, sV, qb, c2, kt * kBlockKeys, nk, g, ln, lane16, half16);
+          fwd_block<T, false>(st, sK, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
       }
+      stage = stage == kFwdStages - 1 ? 0 : stage + 1;
     }
     __syncthreads();  // the ring is free for the next item
 

@@ -126,21 +126,45 @@ static __device__ __forceinline__ int tile_off(int row, int col) {
   return row * 64 + ((((col >> 3) ^ swz(row)) << 3) | (col & 7));
 }
 
-// A operand from a tile: row `row`, elements col .. col+7 (col a multiple of 8).
-static __device__ __forceinline__ u32x4 lds_read_row8(const uint16_t* tile, int row, int col) {
-  return *reinterpret_cast<const u32x4*>(tile + tile_off(row, col));
-}
+// Per-lane offsets of the operand reads, computed once per kernel.  Moving by
+// a multiple of 16 rows leaves swz() unchanged, so stepping through a tile only
+// adds constants (which the LDS instructions carry as immediates).
+//
+// RowRead: A (or B) operand whose contraction runs along the tile's COLUMNS:
+// the lane reads row ln (+32 per row block), columns 16t + 8g .. +7.
+struct RowRead {
+  int off[4];
+  __device__ __forceinline__ RowRead(int ln, int g) {
+#pragma unroll
+    for (int t = 0; t < 4; t++) off[t] = tile_off(ln, 16 * t + 8 * g);
+  }
+  // rows 32*rb + ln, columns 16t + 8g .. +7
+  __device__ __forceinline__ u32x4 read(const uint16_t* tile, int rb, int t) const {
+    return *reinterpret_cast<const u32x4*>(tile + off[t] + 2048 * rb);
+  }
+};
 
-// A operand for a contraction over the tile's ROWS: the lane gets, for column
-// col16 + lane16, rows base+{0..3} and base+8+{0..3}.  `lane16 = lane % 16`
-// picks the address this lane contributes to its 16-lane group.
-static __device__ __forceinline__ u32x4 lds_read_col8(const uint16_t* tile, int base, int col16,
-                                                      int lane16) {
-  const int row = base + (lane16 >> 2), col = col16 + 4 * (lane16 & 3);
-  u32x2 a = lds_read_tr16(tile + tile_off(row, col));
-  u32x2 b = lds_read_tr16(tile + tile_off(row + 8, col));
-  return u32x4{a[0], a[1], b[0], b[1]};
-}
+// ColRead: A operand whose contraction runs along the tile's ROWS (transpose
+// reads): for column 32cb + (lane % 32) the lane gets rows
+// 16*step + {4g..4g+3, 8+4g..8+4g+3} - exactly the rows whose values sit in
+// registers 8t..8t+7 of a C tile (see the layout note at the top).
+struct ColRead {
+  int off[2][2];  // [column block][second half of the eight rows]
+  __device__ __forceinline__ ColRead(int lane) {
+    const int g = lane >> 5, half16 = (lane >> 4) & 1, lane16 = lane & 15;
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+      for (int hh = 0; hh < 2; hh++)
+        off[cb][hh] = tile_off(4 * g + (lane16 >> 2) + 8 * hh, 32 * cb + 16 * half16 + 4 * (lane16 & 3));
+  }
+  // rows 16*step + ..., column block cb
+  __device__ __forceinline__ u32x4 read(const uint16_t* tile, int step, int cb) const {
+    u32x2 a = lds_read_tr16(tile + off[cb][0] + 1024 * step);
+    u32x2 b = lds_read_tr16(tile + off[cb][1] + 1024 * step);
+    return u32x4{a[0], a[1], b[0], b[1]};
+  }
+};
 
 // ---------------------------------------------------------------------------
 // Global -> LDS without passing through registers (global_load_lds_dwordx4):
@@ -177,6 +201,14 @@ struct DmaLane {
     chunk = (lane & 7) ^ swz(row);
   }
 };
+
+// Start moving 64 full rows: pa / pb point at this lane's chunk in its two rows.
+static __device__ __forceinline__ void dma_tile_full(const uint16_t* pa, const uint16_t* pb,
+                                                     int wave, uint32_t tile_addr) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(tile_addr + 1024u * wave);
+  dma16(pa, m0);
+  dma16(pb, m0 + 4096u);
+}
 
 // Start moving rows [row0, row0 + 64) of a packed tensor (rows clamped to
 // last_row, so the tail of a short sequence repeats its last valid row instead
