@@ -4,23 +4,28 @@
 //
 // One workgroup (4 wavefronts) takes one tile of 128 query rows of one
 // (sequence, head); wavefront w owns rows 32w..32w+31.  Keys and values move
-// 64 rows at a time from HBM straight into a ring of LDS stages, two blocks
-// ahead of the one being computed, with one barrier per step.
+// 64 rows at a time from HBM straight into a ring of four LDS stages, up to
+// three blocks ahead of the one being soft-maxed, with one barrier per step.
+//
 // The scores are produced TRANSPOSED, S^T = K Q^T, so that in the MFMA result
 // layout every lane holds 16 keys of ONE query: the row maximum and row sum
 // are then per-lane reductions plus a single exchange with the lane 32 away,
 // and the probabilities are already in the operand layout of the second
 // product O^T = V^T P^T.
 //
-// The softmax is the part that competes with the matrix cores for issue
-// slots (one v_exp_f32 costs as much as a quarter of the MFMA work a score
-// needs), so it is kept to: one max3 per two scores, one fused multiply-add
-// and one exp2 per score, one pack per two scores, one dot2 per two scores
-// for the row sum.  The running maximum is only raised when a tile exceeds it
-// by more than kRescaleStep (in log2 units); until then probabilities may
-// exceed 1 (by at most 2^kRescaleStep, harmless in fp16/bf16 and fp32), and
-// the rescaling of the accumulators is skipped.  The result is the same
-// softmax: the maximum cancels between numerator and row sum.
+// The softmax competes with the matrix cores for issue slots (a v_exp_f32
+// costs a quarter of the MFMA time a score needs), and two wavefronts sharing
+// a SIMD fall into lock step rather than filling each other's gaps.  So each
+// wavefront overlaps the two units itself: the MFMAs that compute the scores of
+// block i+1 are woven through the exponentials of block i.  The vector work per
+// score is one fused multiply-add, one exp2, half a max3, half a pack and half
+// a dot2 (row sum).
+//
+// The running maximum is only raised when a block exceeds it by more than
+// kRescaleStep (log2 units); until then probabilities may exceed 1 (by at most
+// 2^kRescaleStep: harmless in fp16/bf16 and fp32) and the accumulators are not
+// rescaled.  The result is the same softmax: the maximum cancels between
+// numerator and row sum.
 #pragma once
 #include "kernel_args.h"
 #include "mfma_tiles.h"
@@ -28,62 +33,58 @@
 namespace fmha {
 
 constexpr float kRescaleStep = 8.f;
+constexpr int kRing = 4;  // LDS ring: one K and one V tile per stage (16 KB)
 
-constexpr int kFwdStages = 3;                 // LDS ring: K and V tile per stage (16 KB)
-constexpr int kFwdAhead = kFwdStages - 1;     // blocks in flight ahead of the compute
-
-template <typename T>
-struct FwdState {
-  f32x16 oacc[2];  // O^T: column = query ln; oacc[cb][r] is channel 32cb + 8(r/4) + 4g + r%4
-  float m_run;     // running maximum, log2 domain (scaled by scale*log2 e)
-  float l_run;     // this lane's share of the running row sum
+struct FwdAcc {
+  f32x16 o[2];  // O^T: column = query ln; o[cb][r] is channel 32cb + 8(r/4) + 4g + r%4
+  float m_run;  // running maximum, log2 domain (scaled by |scale|*log2 e)
+  float l_run;  // this lane's share of the running row sum
 };
 
-// One block of 64 keys for one wavefront.  RAGGED: keys at or beyond nk (only
-// possible in a sequence's last block) are excluded.
-//
-// The LDS reads of each product are issued together ahead of its MFMAs (the
-// sched_barriers keep the compiler from sinking each read next to its use,
-// which would serialise LDS latency with every MFMA); the transpose reads of V
-// are in flight during the softmax arithmetic.
-template <typename T, bool RAGGED>
-__device__ __forceinline__ void fwd_block(FwdState<T>& st, const uint16_t* sK, const uint16_t* sV,
-                                          const u32x4 (&qb)[4], float c2, int key_base, int nk,
-                                          int g, const RowRead& rr, const ColRead& cr) {
+// S^T = K Q^T for one block of 64 keys: rows = keys (two blocks of 32), column = query ln
+template <typename T>
+__device__ __forceinline__ void fwd_scores(f32x16 (&s)[2], const uint16_t* sK, const u32x4 (&qb)[4],
+                                           const RowRead& rr) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   u32x4 ka[4][2];
 #pragma unroll
   for (int t = 0; t < 4; t++)
 #pragma unroll
     for (int kb = 0; kb < 2; kb++) ka[t][kb] = rr.read(sK, kb, t);
-  __builtin_amdgcn_sched_barrier(0);
-  // S^T = K Q^T : rows = keys (two blocks of 32), column = query ln
-  f32x16 s[2];
-#pragma unroll
-  for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-    for (int r = 0; r < 16; r++) s[kb][r] = 0.f;
 #pragma unroll
   for (int t = 0; t < 4; t++)
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++) s[kb] = Op<T>::mfma(ka[t][kb], qb[t], s[kb]);
-  __builtin_amdgcn_sched_barrier(0);
-  u32x4 va[2][2][2];  // V^T operands: [key block][16-key step][channel block]
-#pragma unroll
-  for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-    for (int t2 = 0; t2 < 2; t2++)
-#pragma unroll
-      for (int cb = 0; cb < 2; cb++)
-        va[kb][t2][cb] = cr.read(sV, 2 * kb + t2, cb);
-  __builtin_amdgcn_sched_barrier(0);
+    for (int kb = 0; kb < 2; kb++) s[kb] = Op<T>::mfma(ka[t][kb], qb[t], t == 0 ? zero : s[kb]);
+}
 
-  const int key0 = key_base + 4 * g;  // key of s[0][0]
+// One pipeline step of one wavefront over a block of 64 keys:
+//   vector ALU  : soft-max block i, whose scores are in s_cur
+//   matrix core : (HAS_NEXT) scores of block i+1 (keys in sK_next) -> s_next, the MFMAs
+//                 woven through the exponentials; then O^T += V_i^T P_i^T (keys in sV).
+// RAGGED: keys at or beyond nk (only in a sequence's last block) are excluded.
+// Apart from the rare rescale branch after the maximum, the step is
+// straight-line code.
+template <typename T, bool RAGGED, bool HAS_NEXT>
+__device__ __forceinline__ void fwd_step(FwdAcc& acc, const f32x16 (&s_cur)[2], f32x16 (&s_next)[2],
+                                         const uint16_t* sK_next, const uint16_t* sV,
+                                         const u32x4 (&qb)[4], float c2, int key_base, int nk, int g,
+                                         const RowRead& rr, const ColRead& cr) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // operands of the score product are requested first; they arrive under the maximum
+  u32x4 ka[4][2];
+  if (HAS_NEXT) {
+#pragma unroll
+    for (int t = 0; t < 4; t++)
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++) ka[t][kb] = rr.read(sK_next, kb, t);
+  }
+  const int key0 = key_base + 4 * g;      // key of s_cur[0][0]
   float mxs[2] = {-INFINITY, -INFINITY};  // two independent chains
 #pragma unroll
   for (int kb = 0; kb < 2; kb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-      float x = s[kb][r];
+      float x = s_cur[kb][r];
       if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) x = -INFINITY;
       mxs[kb] = fmaxf(mxs[kb], x);
     }
@@ -91,17 +92,34 @@ __device__ __forceinline__ void fwd_block(FwdState<T>& st, const uint16_t* sK, c
   mx = fmaxf(mx, other_half(mx));
   const float m_blk = mx * c2;  // c2 >= 0: the sign of the scale was folded into Q
   // first block: m_run = -inf, so alpha = 0 and the (zero) accumulators stay zero
-  if (__any(m_blk > st.m_run + kRescaleStep)) {
-    const float m_new = m_blk > st.m_run + kRescaleStep ? m_blk : st.m_run;
-    const float alpha = fast_exp2(st.m_run - m_new);
-    st.m_run = m_new;
-    st.l_run *= alpha;
+  if (__any(m_blk > acc.m_run + kRescaleStep)) {
+    const float m_new = m_blk > acc.m_run + kRescaleStep ? m_blk : acc.m_run;
+    const float alpha = fast_exp2(acc.m_run - m_new);
+    acc.m_run = m_new;
+    acc.l_run *= alpha;
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) st.oacc[cb][r] *= alpha;
+      for (int r = 0; r < 16; r++) acc.o[cb][r] *= alpha;
   }
-  const float neg_m = -st.m_run;
+  __builtin_amdgcn_sched_barrier(0);
+
+  // V^T operands: [key block][16-key step][channel block]; they arrive under the exponentials
+  u32x4 va[2][2][2];
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+      for (int cb = 0; cb < 2; cb++) va[kb][t2][cb] = cr.read(sV, 2 * kb + t2, cb);
+  if (HAS_NEXT) {
+#pragma unroll
+    for (int t = 0; t < 4; t++)
+#pragma unroll
+      for (int kb = 0; kb < 2; kb++)
+        s_next[kb] = Op<T>::mfma(ka[t][kb], qb[t], t == 0 ? zero : s_next[kb]);
+  }
+  const float neg_m = -acc.m_run;
   float psum = 0.f;
   u32x4 pb[2][2];  // P^T as B operands: [key block][16-key step]
 #pragma unroll
@@ -109,7 +127,7 @@ __device__ __forceinline__ void fwd_block(FwdState<T>& st, const uint16_t* sK, c
     float p[16];
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-      p[r] = fast_exp2(__builtin_fmaf(s[kb][r], c2, neg_m));
+      p[r] = fast_exp2(__builtin_fmaf(s_cur[kb][r], c2, neg_m));
       if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) p[r] = 0.f;
     }
 #pragma unroll
@@ -123,7 +141,16 @@ __device__ __forceinline__ void fwd_block(FwdState<T>& st, const uint16_t* sK, c
       pb[kb][t2] = w;
     }
   }
-  st.l_run += psum;
+  acc.l_run += psum;
+  if (HAS_NEXT) {
+    // two transpose reads, one MFMA, a dozen vector instructions, eight times over
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 13, 0);
+    }
+  }
   __builtin_amdgcn_sched_barrier(0);
   // O^T += V^T P^T : rows = channels (two blocks of 32), contraction over keys
 #pragma unroll
@@ -132,12 +159,12 @@ __device__ __forceinline__ void fwd_block(FwdState<T>& st, const uint16_t* sK, c
     for (int t2 = 0; t2 < 2; t2++)
 #pragma unroll
       for (int cb = 0; cb < 2; cb++)
-        st.oacc[cb] = Op<T>::mfma(va[kb][t2][cb], pb[kb][t2], st.oacc[cb]);
+        acc.o[cb] = Op<T>::mfma(va[kb][t2][cb], pb[kb][t2], acc.o[cb]);
 }
 
 template <typename T>
 __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) {
-  __shared__ __align__(1024) uint16_t ring[kFwdStages][2][kTileElems];  // [stage][K|V]
+  __shared__ __align__(1024) uint16_t ring[kRing][2][kTileElems];  // [stage][K|V]
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -150,7 +177,7 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
   const RowRead rr(ln, g);
   const ColRead cr(lane);
   const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
-  constexpr uint32_t kStageBytes = 2 * kTileElems * 2, kTileBytes = kTileElems * 2;
+  constexpr uint32_t kTileBytes = kTileElems * 2;
 
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
@@ -163,26 +190,26 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
     const bool wave_on = ti.row0 + 32 * wave < len;  // wavefront has at least one valid row
     const uint16_t* kbase = a.k + (int64_t)r0 * a.k_stride + head * kHeadDim;
     const uint16_t* vbase = a.v + (int64_t)r0 * a.v_stride + head * kHeadDim;
-    const int n_kt = (nk + kBlockKeys - 1) / kBlockKeys;
+    const int n = (nk + kBlockKeys - 1) / kBlockKeys;  // blocks of 64 keys
 
-    // this lane's chunk in its two rows of block 0
+    // Start moving block kt of K and V into ring stage `stage`: 4 pieces per thread.
     const uint16_t* kpa = kbase + dl.row * a.k_stride + dl.chunk * 8;
     const uint16_t* vpa = vbase + dl.row * a.v_stride + dl.chunk * 8;
     auto start_block = [&](int kt, int stage) {
-      const uint32_t st_addr = ring_addr + stage * kStageBytes;
+      const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
       if ((kt + 1) * kBlockKeys <= nk) {
-        const uint16_t* ka_ = kpa + (int64_t)kt * kBlockKeys * a.k_stride;
-        const uint16_t* va_ = vpa + (int64_t)kt * kBlockKeys * a.v_stride;
-        dma_tile_full(ka_, ka_ + 32 * a.k_stride, wave, st_addr);
-        dma_tile_full(va_, va_ + 32 * a.v_stride, wave, st_addr + kTileBytes);
+        const uint16_t* pk = kpa + (int64_t)kt * kBlockKeys * a.k_stride;
+        const uint16_t* pv = vpa + (int64_t)kt * kBlockKeys * a.v_stride;
+        dma_tile_full(pk, pk + 32 * a.k_stride, wave, st_addr);
+        dma_tile_full(pv, pv + 32 * a.v_stride, wave, st_addr + kTileBytes);
       } else {
         dma_tile(kbase, a.k_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr);
         dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
       }
     };
 #pragma unroll
-    for (int kt = 0; kt < kFwdAhead; kt++)
-      if (kt < n_kt) start_block(kt, kt);
+    for (int kt = 0; kt < kRing - 1; kt++)
+      if (kt < n) start_block(kt, kt);
 
     // Q^T as the B operand: column = query ln, slots = channels 16t + 8g .. +7.
     // A negative scale is applied as a sign flip of Q so that the row maximum
@@ -199,41 +226,61 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
       }
     }
 
-    FwdState<T> st;
+    FwdAcc acc;
 #pragma unroll
     for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-      for (int r = 0; r < 16; r++) st.oacc[cb][r] = 0.f;
-    st.m_run = -INFINITY;
-    st.l_run = 0.f;
+      for (int r = 0; r < 16; r++) acc.o[cb][r] = 0.f;
+    acc.m_run = -INFINITY;
+    acc.l_run = 0.f;
 
-    int stage = 0;  // kt % kFwdStages
-    for (int kt = 0; kt < n_kt; kt++) {
-      // this thread's pieces of block kt have landed once at most the pieces of the
-      // blocks started after it (4 per block) are outstanding
-      static_assert(kFwdAhead == 2, "the waits below are written for two blocks in flight");
-      if (n_kt - kt >= 2)
+    // Pipeline: block kt's scores are computed one step early, under block kt-1's
+    // exponentials.  At the top of step kt the pieces of blocks kt and kt+1 must have
+    // landed (kt+1's keys are read in this step); block kt+3 is started into the stage
+    // that block kt-1 occupied.  Each thread has 4 pieces per block in flight.
+    static_assert(kRing == 4, "the waits below are written for a ring of four stages");
+    if (n > 0) {
+      f32x16 sA[2], sB[2];  // scores of even / odd blocks
+      if (n >= 3)
+        wait_vmem<8>();
+      else if (n == 2)
         wait_vmem<4>();
       else
         wait_vmem<0>();
-      __syncthreads();  // everyone's pieces landed; everyone is done with block kt-1's stage
-      const int ahead = stage == 0 ? kFwdStages - 1 : stage - 1;  // (kt + kFwdAhead) % kFwdStages
-      if (kt + kFwdAhead < n_kt) start_block(kt + kFwdAhead, ahead);
-      if (wave_on) {
-        const uint16_t* sK = &ring[0][0][0] + stage * (2 * kTileElems);
-        const uint16_t* sV = sK + kTileElems;
-        if ((kt + 1) * kBlockKeys > nk)
-          fwd_block<T, true>(st, sK, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
-        else
-          fwd_block<T, false>(st, sK, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
+      __syncthreads();
+      if (wave_on) fwd_scores<T>(sA, &ring[0][0][0], qb, rr);
+      auto step = [&](int kt, const f32x16 (&s_cur)[2], f32x16 (&s_next)[2]) {
+        const int left = n - kt;  // blocks not yet soft-maxed, this one included
+        if (left >= 2) {          // block kt+1 has to be complete
+          if (left >= 3)
+            wait_vmem<4>();
+          else
+            wait_vmem<0>();
+          __syncthreads();  // also: everyone is done reading block kt-1's stage
+        }
+        const int stage = kt & 3;
+        if (kt + 3 < n) start_block(kt + 3, (stage + 3) & 3);
+        if (wave_on) {
+          const uint16_t* sV = &ring[0][0][0] + stage * (2 * kTileElems) + kTileElems;
+          const uint16_t* sKn = &ring[0][0][0] + ((stage + 1) & 3) * (2 * kTileElems);
+          if (left >= 2)
+            fwd_step<T, false, true>(acc, s_cur, s_next, sKn, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
+          else if ((kt + 1) * kBlockKeys > nk)
+            fwd_step<T, true, false>(acc, s_cur, s_next, sKn, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
+          else
+            fwd_step<T, false, false>(acc, s_cur, s_next, sKn, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
+        }
+      };
+      for (int kt = 0; kt < n; kt += 2) {
+        step(kt, sA, sB);
+        if (kt + 1 < n) step(kt + 1, sB, sA);
       }
-      stage = stage == kFwdStages - 1 ? 0 : stage + 1;
     }
-    __syncthreads();  // the ring is free for the next item
+    __syncthreads();  // the rings are free for the next item
 
     // epilogue: combine the two half-rows' sums, normalise, store O and LSE
     if (wave_on) {
-      const float l_tot = st.l_run + other_half(st.l_run);
+      const float l_tot = acc.l_run + other_half(acc.l_run);
       const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
       if (qrow < len) {
         uint16_t* op = a.o + (int64_t)(r0 + qrow) * a.o_stride + head * kHeadDim + 4 * g;
@@ -241,13 +288,13 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
         for (int cb = 0; cb < 2; cb++)
 #pragma unroll
           for (int j = 0; j < 4; j++) {
-            u32x2 w = {Op<T>::pack2(st.oacc[cb][4 * j] * inv, st.oacc[cb][4 * j + 1] * inv),
-                       Op<T>::pack2(st.oacc[cb][4 * j + 2] * inv, st.oacc[cb][4 * j + 3] * inv)};
+            u32x2 w = {Op<T>::pack2(acc.o[cb][4 * j] * inv, acc.o[cb][4 * j + 1] * inv),
+                       Op<T>::pack2(acc.o[cb][4 * j + 2] * inv, acc.o[cb][4 * j + 3] * inv)};
             *reinterpret_cast<u32x2*>(op + 32 * cb + 8 * j) = w;
           }
         if (g == 0)
           a.lse[(int64_t)head * a.pb.total_tokens + r0 + qrow] =
-              l_tot > 0.f ? (st.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+              l_tot > 0.f ? (acc.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
       }
     }
   }
