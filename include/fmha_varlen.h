@@ -61,7 +61,7 @@ typedef enum { FMHA_F16 = 0, FMHA_BF16 = 1 } fmha_dtype_t;
  * batch_offset once per mini-batch (Section IV-B-2). */
 #define FMHA_FLAG_REUSE_SCHEDULE 1u
 /* fmha_varlen_bwd only: run one of the two backward passes.  The dQ pass also
- * writes the row sums of dO o O into the workspace; the dK/dV pass reads them,
+ * writes the per-row statistics into the workspace; the dK/dV pass reads them,
  * so a dK/dV-only call must follow a dQ pass on the same workspace and inputs.
  * The output pointers of the skipped pass are still validated but not written. */
 #define FMHA_FLAG_BWD_ONLY_DQ 2u
@@ -91,8 +91,8 @@ typedef struct fmha_varlen_params {
 } fmha_varlen_params_t;
 
 /* Bytes of device workspace for a batch of this shape (tile list; plus, if
- * need_bwd, one fp32 per (token, head) for the row sums of dO o O).  Pure
- * host arithmetic; returns 0 on invalid sizes. */
+ * need_bwd, two fp32 per (token, head): the row sums of dO o O and the
+ * log-sum-exp in base-2 units).  Pure host arithmetic; returns 0 on invalid sizes. */
 size_t fmha_varlen_workspace_size(int32_t batch, int32_t total_tokens, int32_t heads,
                                   int32_t need_bwd);
 

@@ -13,57 +13,106 @@
 // spread over its registers; P and dS then go back in as B operands without
 // passing through LDS, and the per-row statistics (LSE, D) are per-lane
 // scalars in pass 1 and broadcast LDS reads in pass 2.
+//
+// The streamed operand (K and V in pass 1; Q, dO and the row statistics in
+// pass 2) moves from HBM straight into a ring of swizzled LDS stages, two
+// blocks ahead of its use, one barrier per block.
 #pragma once
-#include "fwd_kernel.h"
+#include "kernel_args.h"
+#include "mfma_tiles.h"
 
 namespace fmha {
 
-// Register-staged, padded LDS tiles (row stride 64 + 8 elements).
-constexpr int kLdsRow = 72;
+constexpr int kBwdStages = 3;
 
-__device__ __forceinline__ void load_tile_regs(const uint16_t* __restrict__ base, int64_t stride,
-                                               int row0, int nrows, int tid, u32x4 (&r)[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; i++) {
-    const int c = tid + kThreads * i;
-    const int row = row0 + (c >> 3);
-    r[i] = u32x4{0, 0, 0, 0};
-    if (row < nrows) r[i] = *reinterpret_cast<const u32x4*>(base + row * stride + (c & 7) * 8);
-  }
-}
-
-__device__ __forceinline__ void store_tile_lds(uint16_t* tile, int tid, const u32x4 (&r)[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; i++) {
-    const int c = tid + kThreads * i;
-    *reinterpret_cast<u32x4*>(tile + (c >> 3) * kLdsRow + (c & 7) * 8) = r[i];
-  }
-}
-
-static __device__ __forceinline__ u32x4 pad_read_row8(const uint16_t* tile, int row, int col) {
-  return *reinterpret_cast<const u32x4*>(tile + row * kLdsRow + col);
-}
-
-static __device__ __forceinline__ u32x4 pad_read_col8(const uint16_t* tile, int base, int col16,
-                                                      int lane16) {
-  const uint16_t* p = tile + (base + (lane16 >> 2)) * kLdsRow + col16 + 4 * (lane16 & 3);
-  u32x2 a = lds_read_tr16(p);
-  u32x2 b = lds_read_tr16(p + 8 * kLdsRow);
-  return u32x4{a[0], a[1], b[0], b[1]};
+// registers 8*t2 .. 8*t2+7 of a result tile as one B operand
+template <typename T>
+static __device__ __forceinline__ u32x4 pack8(const float (&x)[16], int t2) {
+  return u32x4{Op<T>::pack2(x[8 * t2 + 0], x[8 * t2 + 1]), Op<T>::pack2(x[8 * t2 + 2], x[8 * t2 + 3]),
+               Op<T>::pack2(x[8 * t2 + 4], x[8 * t2 + 5]), Op<T>::pack2(x[8 * t2 + 6], x[8 * t2 + 7])};
 }
 
 // ---------------------------------------------------------------- pass 1: dQ
+// One block of 64 keys for one wavefront (32 queries).
+template <typename T, bool RAGGED>
+__device__ __forceinline__ void dq_block(f32x16 (&dq)[2], const uint16_t* sK, const uint16_t* sV,
+                                         const u32x4 (&qb)[4], const u32x4 (&gb)[4], float c2,
+                                         float lse2, float dsum, int key_base, int nk, int g,
+                                         const RowRead& rr, const ColRead& cr) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  u32x4 ka[4][2], va[4][2];
+#pragma unroll
+  for (int t = 0; t < 4; t++)
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      ka[t][kb] = rr.read(sK, kb, t);
+      va[t][kb] = rr.read(sV, kb, t);
+    }
+  __builtin_amdgcn_sched_barrier(0);
+  // S^T = K Q^T, dP^T = V dO^T : rows = keys, column = query ln
+  f32x16 s[2], dp[2];
+#pragma unroll
+  for (int t = 0; t < 4; t++)
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      s[kb] = Op<T>::mfma(ka[t][kb], qb[t], t == 0 ? zero : s[kb]);
+      dp[kb] = Op<T>::mfma(va[t][kb], gb[t], t == 0 ? zero : dp[kb]);
+    }
+  __builtin_amdgcn_sched_barrier(0);
+  u32x4 kT[2][2][2];  // K^T operands: [key block][16-key step][channel block]
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+      for (int cb = 0; cb < 2; cb++) kT[kb][t2][cb] = cr.read(sK, 2 * kb + t2, cb);
+  __builtin_amdgcn_sched_barrier(0);
+  const int key0 = key_base + 4 * g;
+  u32x4 dsb[2][2];  // dS^T as B operands
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++) {
+    float ds[16];
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      float p = fast_exp2(__builtin_fmaf(s[kb][r], c2, -lse2));
+      if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) p = 0.f;
+      ds[r] = p * (dp[kb][r] - dsum);
+    }
+#pragma unroll
+    for (int t2 = 0; t2 < 2; t2++) dsb[kb][t2] = pack8<T>(ds, t2);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // dQ^T += K^T dS^T : rows = channels, contraction over keys
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+      for (int cb = 0; cb < 2; cb++) dq[cb] = Op<T>::mfma(kT[kb][t2][cb], dsb[kb][t2], dq[cb]);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
-  __shared__ __align__(16) uint16_t sK[kBlockKeys * kLdsRow];
-  __shared__ __align__(16) uint16_t sV[kBlockKeys * kLdsRow];
+  __shared__ __align__(1024) uint16_t ring[kBwdStages][2][kTileElems];  // [stage][K|V]
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
-  const int g = lane >> 5, ln = lane & 31, lane16 = lane & 15, half16 = (lane >> 4) & 1;
+  const int g = lane >> 5, ln = lane & 31;
   const int heads = a.pb.heads;
   const int n_items = *a.pb.n_tiles * heads;
   const float c2 = a.pb.scale * kLog2e;
+  const DmaLane dl(wave, lane);
+  const RowRead rr(ln, g);
+  const ColRead cr(lane);
+  const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
+  constexpr uint32_t kTileBytes = kTileElems * 2;
+
+  // one entry behind each statistics array stands for "row past the end" in pass 2:
+  // LSE = +inf makes its probabilities vanish
+  if (blockIdx.x == 0 && tid == 0) {
+    a.lse2[(int64_t)heads * a.pb.total_tokens] = INFINITY;
+    a.dsum[(int64_t)heads * a.pb.total_tokens] = 0.f;
+  }
 
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
@@ -77,6 +126,24 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
     const bool row_on = qrow < len;
     const uint16_t* kbase = a.k + (int64_t)r0 * a.k_stride + head * kHeadDim;
     const uint16_t* vbase = a.v + (int64_t)r0 * a.v_stride + head * kHeadDim;
+    const int n = (nk + kBlockKeys - 1) / kBlockKeys;
+
+    const uint16_t* kpa = kbase + dl.row * a.k_stride + dl.chunk * 8;
+    const uint16_t* vpa = vbase + dl.row * a.v_stride + dl.chunk * 8;
+    auto start_block = [&](int kt, int stage) {  // 4 pieces per thread
+      const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
+      if ((kt + 1) * kBlockKeys <= nk) {
+        const uint16_t* pk = kpa + (int64_t)kt * kBlockKeys * a.k_stride;
+        const uint16_t* pv = vpa + (int64_t)kt * kBlockKeys * a.v_stride;
+        dma_tile_full(pk, pk + 32 * a.k_stride, wave, st_addr);
+        dma_tile_full(pv, pv + 32 * a.v_stride, wave, st_addr + kTileBytes);
+      } else {
+        dma_tile(kbase, a.k_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr);
+        dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
+      }
+    };
+    if (n > 0) start_block(0, 0);
+    if (n > 1) start_block(1, 1);
 
     // Q^T and dO^T as B operands (column = query ln, slots = channels 16t+8g..+7),
     // and D = sum_c dO*O over this lane's 32 channels, completed with the other half.
@@ -100,7 +167,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
       dsum += other_half(dsum);
       const int64_t si = (int64_t)head * a.pb.total_tokens + tok;
       lse2 = a.lse[si] * kLog2e;
-      if (row_on && g == 0) a.dsum[si] = dsum;
+      if (row_on && g == 0) {
+        a.dsum[si] = dsum;
+        a.lse2[si] = lse2;
+      }
     }
 
     f32x16 dq[2];  // dQ^T: column = query ln, rows = channels
@@ -109,68 +179,27 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; r++) dq[cb][r] = 0.f;
 
-    const int n_kt = (nk + kBlockKeys - 1) / kBlockKeys;
-    u32x4 kreg[2], vreg[2];
-    if (n_kt > 0) {
-      load_tile_regs(kbase, a.k_stride, 0, nk, tid, kreg);
-      load_tile_regs(vbase, a.v_stride, 0, nk, tid, vreg);
-      store_tile_lds(sK, tid, kreg);
-      store_tile_lds(sV, tid, vreg);
-    }
-    __syncthreads();
-
-    for (int kt = 0; kt < n_kt; kt++) {
-      const bool more = kt + 1 < n_kt;
-      if (more) {
-        load_tile_regs(kbase, a.k_stride, (kt + 1) * kBlockKeys, nk, tid, kreg);
-        load_tile_regs(vbase, a.v_stride, (kt + 1) * kBlockKeys, nk, tid, vreg);
-      }
+    int stage = 0;
+    for (int kt = 0; kt < n; kt++) {
+      // block kt has landed once at most block kt+1's 4 pieces are outstanding
+      if (kt + 1 < n)
+        wait_vmem<4>();
+      else
+        wait_vmem<0>();
+      __syncthreads();  // everyone's pieces; and everyone is done with block kt-1's stage
+      const int ahead = stage == 0 ? kBwdStages - 1 : stage - 1;  // (kt + 2) % 3
+      if (kt + 2 < n) start_block(kt + 2, ahead);
       if (wave_on) {
-        const int key0 = kt * kBlockKeys + 4 * g;
-        const bool ragged = key0 - 4 * g + kBlockKeys > nk;
-        u32x4 dsb[2][2];  // dS^T as B operands
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-          f32x16 s, dp;
-#pragma unroll
-          for (int r = 0; r < 16; r++) s[r] = dp[r] = 0.f;
-#pragma unroll
-          for (int t = 0; t < 4; t++) {
-            s = Op<T>::mfma(pad_read_row8(sK, 32 * kb + ln, 16 * t + 8 * g), qb[t], s);
-            dp = Op<T>::mfma(pad_read_row8(sV, 32 * kb + ln, 16 * t + 8 * g), gb[t], dp);
-          }
-          float ds[16];
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            float p = fast_exp2(s[r] * c2 - lse2);
-            if (ragged && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) p = 0.f;
-            ds[r] = p * (dp[r] - dsum);
-          }
-#pragma unroll
-          for (int t2 = 0; t2 < 2; t2++)
-            dsb[kb][t2] = u32x4{Op<T>::pack2(ds[8 * t2 + 0], ds[8 * t2 + 1]),
-                                Op<T>::pack2(ds[8 * t2 + 2], ds[8 * t2 + 3]),
-                                Op<T>::pack2(ds[8 * t2 + 4], ds[8 * t2 + 5]),
-                                Op<T>::pack2(ds[8 * t2 + 6], ds[8 * t2 + 7])};
-        }
-        // dQ^T += K^T dS^T : rows = channels, contraction over keys
-#pragma unroll
-        for (int cb = 0; cb < 2; cb++)
-#pragma unroll
-          for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-            for (int t2 = 0; t2 < 2; t2++)
-              dq[cb] = Op<T>::mfma(
-                  pad_read_col8(sK, 32 * kb + 16 * t2 + 4 * g, 32 * cb + 16 * half16, lane16),
-                  dsb[kb][t2], dq[cb]);
+        const uint16_t* sK = &ring[0][0][0] + stage * (2 * kTileElems);
+        const uint16_t* sV = sK + kTileElems;
+        if ((kt + 1) * kBlockKeys > nk)
+          dq_block<T, true>(dq, sK, sV, qb, gb, c2, lse2, dsum, kt * kBlockKeys, nk, g, rr, cr);
+        else
+          dq_block<T, false>(dq, sK, sV, qb, gb, c2, lse2, dsum, kt * kBlockKeys, nk, g, rr, cr);
       }
-      __syncthreads();
-      if (more) {
-        store_tile_lds(sK, tid, kreg);
-        store_tile_lds(sV, tid, vreg);
-      }
-      __syncthreads();
+      stage = stage == kBwdStages - 1 ? 0 : stage + 1;
     }
+    __syncthreads();  // the ring is free for the next item
 
     if (row_on) {
       const float sc = a.pb.scale;
@@ -188,19 +217,100 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
 }
 
 // ------------------------------------------------------------ pass 2: dK, dV
+struct DkvStage {
+  uint16_t q[kTileElems];   // 64 queries x 64 channels, swizzled
+  uint16_t g[kTileElems];   // dO, same
+  float stat[4][64];        // [0] = LSE*log2(e), [1] = D of the 64 queries; [2], [3] unused
+};
+
+// One block of 32 queries (rows 32*qb.. of the stage) for one wavefront (32 keys).
+// No masking is needed here: query rows past the end of the sequence carry
+// LSE = +inf in the stage (so P = 0), and the columns of keys that are masked
+// or past the end are independent of all others and are simply not stored.
+template <typename T>
+__device__ __forceinline__ void dkv_block(f32x16 (&dk)[2], f32x16 (&dv)[2], const DkvStage* st,
+                                          int qb, const u32x4 (&kb4)[4], const u32x4 (&vb4)[4],
+                                          float c2, int g, const RowRead& rr, const ColRead& cr) {
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  u32x4 qa[4], ga[4];
+#pragma unroll
+  for (int t = 0; t < 4; t++) {
+    qa[t] = rr.read(st->q, qb, t);
+    ga[t] = rr.read(st->g, qb, t);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // S = Q K^T, dP = dO V^T : rows = queries (32), column = key ln
+  f32x16 s, dp;
+#pragma unroll
+  for (int t = 0; t < 4; t++) {
+    s = Op<T>::mfma(qa[t], kb4[t], t == 0 ? zero : s);
+    dp = Op<T>::mfma(ga[t], vb4[t], t == 0 ? zero : dp);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // rows 32qb + 8j + 4g + {0..3}: their statistics sit side by side
+  float4 l4[4], d4[4];
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    l4[j] = *reinterpret_cast<const float4*>(&st->stat[0][32 * qb + 8 * j + 4 * g]);
+    d4[j] = *reinterpret_cast<const float4*>(&st->stat[1][32 * qb + 8 * j + 4 * g]);
+  }
+  u32x4 gT[2][2];  // dO^T operands: [16-query step][channel block]
+#pragma unroll
+  for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++) gT[t2][cb] = cr.read(st->g, 2 * qb + t2, cb);
+  __builtin_amdgcn_sched_barrier(0);
+  float p[16], ds[16];
+#pragma unroll
+  for (int j = 0; j < 4; j++) {
+    const float lv[4] = {l4[j].x, l4[j].y, l4[j].z, l4[j].w};
+    const float dvv[4] = {d4[j].x, d4[j].y, d4[j].z, d4[j].w};
+#pragma unroll
+    for (int e = 0; e < 4; e++) {
+      const float pe = fast_exp2(__builtin_fmaf(s[4 * j + e], c2, -lv[e]));
+      p[4 * j + e] = pe;
+      ds[4 * j + e] = pe * (dp[4 * j + e] - dvv[e]);
+    }
+  }
+  u32x4 pb[2], dsb[2];
+#pragma unroll
+  for (int t2 = 0; t2 < 2; t2++) {
+    pb[t2] = pack8<T>(p, t2);
+    dsb[t2] = pack8<T>(ds, t2);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // Q^T operands are requested now and arrive under the dV MFMAs
+  u32x4 qT[2][2];
+#pragma unroll
+  for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++) qT[t2][cb] = cr.read(st->q, 2 * qb + t2, cb);
+  // dV^T += dO^T P, dK^T += Q^T dS : rows = channels, contraction over queries
+#pragma unroll
+  for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++) dv[cb] = Op<T>::mfma(gT[t2][cb], pb[t2], dv[cb]);
+#pragma unroll
+  for (int t2 = 0; t2 < 2; t2++)
+#pragma unroll
+    for (int cb = 0; cb < 2; cb++) dk[cb] = Op<T>::mfma(qT[t2][cb], dsb[t2], dk[cb]);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
-  __shared__ __align__(16) uint16_t sQ[kBlockKeys * kLdsRow];
-  __shared__ __align__(16) uint16_t sG[kBlockKeys * kLdsRow];  // dO
-  __shared__ __align__(16) float sLse[kBlockKeys];             // LSE * log2(e); +inf on pad rows
-  __shared__ __align__(16) float sD[kBlockKeys];
+  __shared__ __align__(1024) DkvStage ring[kBwdStages];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
-  const int g = lane >> 5, ln = lane & 31, lane16 = lane & 15, half16 = (lane >> 4) & 1;
+  const int g = lane >> 5, ln = lane & 31;
   const int heads = a.pb.heads;
   const int n_items = *a.pb.n_tiles * heads;
   const float c2 = a.pb.scale * kLog2e;
+  const DmaLane dl(wave, lane);
+  const RowRead rr(ln, g);
+  const ColRead cr(lane);
+  const uint32_t ring_addr = lds_addr(&ring[0]);
+  constexpr uint32_t kStageBytes = sizeof(DkvStage), kTileBytes = kTileElems * 2;
 
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
@@ -209,14 +319,39 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
     const int len = a.pb.cu[ti.seq + 1] - r0;
     int nk = a.pb.seqused ? min(a.pb.seqused[ti.seq], len) : len;
     nk = nk < 0 ? 0 : nk;
-    const int krow = ti.row0 + 32 * wave + ln;       // this lane's key, within the sequence
-    const bool wave_on = ti.row0 + 32 * wave < nk;   // wavefront owns at least one live key
-    const bool tile_on = ti.row0 < nk;               // uniform over the workgroup
+    const int krow = ti.row0 + 32 * wave + ln;      // this lane's key, within the sequence
+    const bool wave_on = ti.row0 + 32 * wave < nk;  // wavefront owns at least one live key
+    const bool tile_on = ti.row0 < nk;              // uniform over the workgroup
     const bool key_on = krow < nk;
     const uint16_t* qbase = a.q + (int64_t)r0 * a.q_stride + head * kHeadDim;
     const uint16_t* gbase = a.d_o + (int64_t)r0 * a.do_stride + head * kHeadDim;
-    const float* lsebase = a.lse + (int64_t)head * a.pb.total_tokens + r0;
-    const float* dbase = a.dsum + (int64_t)head * a.pb.total_tokens + r0;
+    // statistics: wavefront 0 moves LSE*log2e, wavefront 1 moves D (2 and 3 repeat them
+    // into the unused quarter of the stage so that every thread has the same piece count).
+    // Rows past the end of the sequence read the +inf / 0 that pass 1 left behind the arrays.
+    const float* stat_arr = (wave & 1) ? a.dsum : a.lse2;
+    const float* stat_src = stat_arr + (int64_t)head * a.pb.total_tokens + r0;
+    const float* stat_pad = stat_arr + (int64_t)heads * a.pb.total_tokens;
+    const int n = tile_on ? (len + kBlockKeys - 1) / kBlockKeys : 0;  // query blocks
+
+    const uint16_t* qpa = qbase + dl.row * a.q_stride + dl.chunk * 8;
+    const uint16_t* gpa = gbase + dl.row * a.do_stride + dl.chunk * 8;
+    auto start_block = [&](int qt, int stage) {  // 5 pieces per thread
+      const uint32_t st_addr = ring_addr + stage * kStageBytes;
+      if ((qt + 1) * kBlockKeys <= len) {
+        const uint16_t* pq = qpa + (int64_t)qt * kBlockKeys * a.q_stride;
+        const uint16_t* pg = gpa + (int64_t)qt * kBlockKeys * a.do_stride;
+        dma_tile_full(pq, pq + 32 * a.q_stride, wave, st_addr);
+        dma_tile_full(pg, pg + 32 * a.do_stride, wave, st_addr + kTileBytes);
+      } else {
+        dma_tile(qbase, a.q_stride, qt * kBlockKeys, len - 1, dl, wave, st_addr);
+        dma_tile(gbase, a.do_stride, qt * kBlockKeys, len - 1, dl, wave, st_addr + kTileBytes);
+      }
+      const uint32_t m0 = __builtin_amdgcn_readfirstlane(st_addr + 2 * kTileBytes + 256u * wave);
+      const int srow = qt * kBlockKeys + lane;
+      dma4(srow < len ? stat_src + srow : stat_pad, m0);
+    };
+    if (n > 0) start_block(0, 0);
+    if (n > 1) start_block(1, 1);
 
     // K^T and V^T as B operands: column = key ln, slots = channels 16t+8g..+7
     u32x4 kb4[4], vb4[4];
@@ -237,100 +372,34 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; r++) dk[cb][r] = dv[cb][r] = 0.f;
 
-    const int n_qt = tile_on ? (len + kBlockKeys - 1) / kBlockKeys : 0;
-    u32x4 qreg[2], greg[2];
-    float lreg = 0.f, dreg = 0.f;
-    auto load_stats = [&](int q0) {
-      if (tid < kBlockKeys) {
-        const int r = q0 + tid;
-        lreg = r < len ? lsebase[r] * kLog2e : INFINITY;
-        dreg = r < len ? dbase[r] : 0.f;
+    int stage = 0;
+    for (int qt = 0; qt < n; qt++) {
+      if (qt + 1 < n)
+        wait_vmem<5>();
+      else
+        wait_vmem<0>();
+      __syncthreads();
+      const int ahead = stage == 0 ? kBwdStages - 1 : stage - 1;
+      if (qt + 2 < n) start_block(qt + 2, ahead);
+      if (wave_on) {
+        const DkvStage* st = &ring[stage];
+        dkv_block<T>(dk, dv, st, 0, kb4, vb4, c2, g, rr, cr);
+        if (qt * kBlockKeys + 32 < len) dkv_block<T>(dk, dv, st, 1, kb4, vb4, c2, g, rr, cr);
       }
-    };
-    auto store_stats = [&]() {
-      if (tid < kBlockKeys) {
-        sLse[tid] = lreg;
-        sD[tid] = dreg;
-      }
-    };
-    if (n_qt > 0) {
-      load_tile_regs(qbase, a.q_stride, 0, len, tid, qreg);
-      load_tile_regs(gbase, a.do_stride, 0, len, tid, greg);
-      load_stats(0);
-      store_tile_lds(sQ, tid, qreg);
-      store_tile_lds(sG, tid, greg);
-      store_stats();
+      stage = stage == kBwdStages - 1 ? 0 : stage + 1;
     }
     __syncthreads();
 
-    for (int qt = 0; qt < n_qt; qt++) {
-      const bool more = qt + 1 < n_qt;
-      if (more) {
-        load_tile_regs(qbase, a.q_stride, (qt + 1) * kBlockKeys, len, tid, qreg);
-        load_tile_regs(gbase, a.do_stride, (qt + 1) * kBlockKeys, len, tid, greg);
-        load_stats((qt + 1) * kBlockKeys);
-      }
-      if (wave_on) {
-#pragma unroll
-        for (int qb = 0; qb < 2; qb++) {
-          // S = Q K^T, dP = dO V^T : rows = queries (32), column = key ln
-          f32x16 s, dp;
-#pragma unroll
-          for (int r = 0; r < 16; r++) s[r] = dp[r] = 0.f;
-#pragma unroll
-          for (int t = 0; t < 4; t++) {
-            s = Op<T>::mfma(pad_read_row8(sQ, 32 * qb + ln, 16 * t + 8 * g), kb4[t], s);
-            dp = Op<T>::mfma(pad_read_row8(sG, 32 * qb + ln, 16 * t + 8 * g), vb4[t], dp);
-          }
-          float p[16], ds[16];
-#pragma unroll
-          for (int j = 0; j < 4; j++) {
-            // rows 32qb + 8j + 4g + {0..3}: their statistics sit side by side in LDS
-            const float4 l4 = *reinterpret_cast<const float4*>(&sLse[32 * qb + 8 * j + 4 * g]);
-            const float4 d4 = *reinterpret_cast<const float4*>(&sD[32 * qb + 8 * j + 4 * g]);
-            const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
-            const float dvv[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-            for (int e = 0; e < 4; e++) {
-              float pe = fast_exp2(s[4 * j + e] * c2 - lv[e]);  // pad rows: exp2(-inf) = 0
-              pe = key_on ? pe : 0.f;
-              p[4 * j + e] = pe;
-              ds[4 * j + e] = pe * (dp[4 * j + e] - dvv[e]);
-            }
-          }
-          // dV^T += dO^T P, dK^T += Q^T dS : rows = channels, contraction over queries
-#pragma unroll
-          for (int t2 = 0; t2 < 2; t2++) {
-            const u32x4 pb = {Op<T>::pack2(p[8 * t2 + 0], p[8 * t2 + 1]),
-                              Op<T>::pack2(p[8 * t2 + 2], p[8 * t2 + 3]),
-                              Op<T>::pack2(p[8 * t2 + 4], p[8 * t2 + 5]),
-                              Op<T>::pack2(p[8 * t2 + 6], p[8 * t2 + 7])};
-            const u32x4 dsb = {Op<T>::pack2(ds[8 * t2 + 0], ds[8 * t2 + 1]),
-                               Op<T>::pack2(ds[8 * t2 + 2], ds[8 * t2 + 3]),
-                               Op<T>::pack2(ds[8 * t2 + 4], ds[8 * t2 + 5]),
-                               Op<T>::pack2(ds[8 * t2 + 6], ds[8 * t2 + 7])};
-#pragma unroll
-            for (int cb = 0; cb < 2; cb++) {
-              const int base = 32 * qb + 16 * t2 + 4 * g, col = 32 * cb + 16 * half16;
-              dv[cb] = Op<T>::mfma(pad_read_col8(sG, base, col, lane16), pb, dv[cb]);
-              dk[cb] = Op<T>::mfma(pad_read_col8(sQ, base, col, lane16), dsb, dk[cb]);
-            }
-          }
-        }
-      }
-      __syncthreads();
-      if (more) {
-        store_tile_lds(sQ, tid, qreg);
-        store_tile_lds(sG, tid, greg);
-        store_stats();
-      }
-      __syncthreads();
-    }
-
     // every row of the tile is written: live keys get their gradients, keys
-    // masked by seqused get zeros (their accumulators never left zero)
+    // masked by seqused get zeros
     if (krow < len) {
-      const float sc = a.pb.scale;
+      const float sc = key_on ? a.pb.scale : 0.f;
+      if (!key_on) {
+#pragma unroll
+        for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) dv[cb][r] = dk[cb][r] = 0.f;
+      }
       const int64_t tok = r0 + krow;
       uint16_t* kp = a.dk + tok * a.dk_stride + head * kHeadDim + 4 * g;
       uint16_t* vp = a.dv + tok * a.dv_stride + head * kHeadDim + 4 * g;

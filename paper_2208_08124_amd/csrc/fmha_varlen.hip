@@ -37,7 +37,8 @@ struct Workspace {
   int32_t* count;
   fmha::TileItem* list;
   float* dsum;
-  size_t count_off, list_off, dsum_off, bytes_fwd, bytes_bwd;
+  float* lse2;
+  size_t count_off, list_off, dsum_off, lse2_off, bytes_fwd, bytes_bwd;
 };
 
 Workspace carve(void* base, int64_t batch, int64_t total_tokens, int64_t heads) {
@@ -47,11 +48,15 @@ Workspace carve(void* base, int64_t batch, int64_t total_tokens, int64_t heads) 
   const size_t list_bytes = sizeof(fmha::TileItem) * (size_t)(tile_capacity(batch, total_tokens) + 1);
   w.dsum_off = round_up(w.list_off + list_bytes, kAlign);
   w.bytes_fwd = w.dsum_off;
-  w.bytes_bwd = w.dsum_off + round_up(sizeof(float) * (size_t)total_tokens * (size_t)heads, kAlign);
+  // one float per (token, head) plus one pad entry
+  const size_t stat_bytes = round_up(sizeof(float) * ((size_t)total_tokens * (size_t)heads + 1), kAlign);
+  w.lse2_off = w.dsum_off + stat_bytes;
+  w.bytes_bwd = w.lse2_off + stat_bytes;
   char* b = static_cast<char*>(base);
   w.count = reinterpret_cast<int32_t*>(b + w.count_off);
   w.list = reinterpret_cast<fmha::TileItem*>(b + w.list_off);
   w.dsum = reinterpret_cast<float*>(b + w.dsum_off);
+  w.lse2 = reinterpret_cast<float*>(b + w.lse2_off);
   return w;
 }
 
@@ -229,6 +234,7 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   a.d_o = static_cast<const uint16_t*>(d_o);
   a.lse = lse;
   a.dsum = w.dsum;
+  a.lse2 = w.lse2;
   a.dq = static_cast<uint16_t*>(dq);
   a.dk = static_cast<uint16_t*>(dk);
   a.dv = static_cast<uint16_t*>(dv);

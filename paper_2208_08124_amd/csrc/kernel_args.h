@@ -36,7 +36,8 @@ struct BwdArgs {
   Problem pb;
   const uint16_t *q, *k, *v, *o, *d_o;
   const float* lse;  // [H, T]
-  float* dsum;       // [H, T] rowsum(dO o O), workspace
+  float* dsum;       // [H, T] rowsum(dO o O), workspace (written by the dQ pass)
+  float* lse2;       // [H, T] lse * log2(e), workspace (written by the dQ pass)
   uint16_t *dq, *dk, *dv;
   int64_t q_stride, k_stride, v_stride, o_stride, do_stride, dq_stride, dk_stride, dv_stride;
 };

@@ -186,6 +186,14 @@ static __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_byte
                : "memory");
 }
 
+// Same for 4 bytes per lane: the wavefront's 64 dwords land at m0 + 4*lane.
+static __device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off"
+               :
+               : "s"(lds_byte_addr), "v"(gptr)
+               : "memory");
+}
+
 template <int N>
 static __device__ __forceinline__ void wait_vmem() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
