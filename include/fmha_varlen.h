@@ -117,10 +117,11 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
                     void* dv, void* stream);
 
 /* Number of 128-row tiles the schedule holds at most for this shape (host
- * arithmetic, the launch is sized by it), and a device-to-host-free way for
- * tests to locate the tile list inside the workspace: the list starts at byte
- * offset *list_offset, holds int32 pairs (sequence, first row within it), and
- * its length is the int32 at byte offset *count_offset. */
+ * arithmetic), and a device-to-host-free way for tests to locate the tile list
+ * inside the workspace: the list starts at byte offset *list_offset and holds
+ * int32 quadruples (packed row at which the sequence starts, its length, its
+ * number of attended keys, first row of the tile within the sequence); its
+ * length is the int32 at byte offset *count_offset. */
 int32_t fmha_varlen_schedule_info(int32_t batch, int32_t total_tokens, int32_t max_seqlen,
                                   size_t* count_offset, size_t* list_offset);
 

@@ -114,13 +114,17 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
     a.dsum[(int64_t)heads * a.pb.total_tokens] = 0.f;
   }
 
+  // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
+  // next item is fetched while the current one is computed.
+  TileItem ti_next = a.pb.tiles[(blockIdx.x < n_items ? blockIdx.x : 0) / heads];
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
-    const TileItem ti = a.pb.tiles[item / heads];
-    const int r0 = a.pb.cu[ti.seq];
-    const int len = a.pb.cu[ti.seq + 1] - r0;
-    int nk = a.pb.seqused ? min(a.pb.seqused[ti.seq], len) : len;
-    nk = nk < 0 ? 0 : nk;
+    const TileItem ti = ti_next;
+    {
+      const int nxt = item + gridDim.x;
+      ti_next = a.pb.tiles[(nxt < n_items ? nxt : item) / heads];
+    }
+    const int r0 = ti.r0, len = ti.len, nk = ti.nk;
     const int qrow = ti.row0 + 32 * wave + ln;
     const bool wave_on = ti.row0 + 32 * wave < len;
     const bool row_on = qrow < len;
@@ -312,13 +316,17 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
   const uint32_t ring_addr = lds_addr(&ring[0]);
   constexpr uint32_t kStageBytes = sizeof(DkvStage), kTileBytes = kTileElems * 2;
 
+  // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
+  // next item is fetched while the current one is computed.
+  TileItem ti_next = a.pb.tiles[(blockIdx.x < n_items ? blockIdx.x : 0) / heads];
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
-    const TileItem ti = a.pb.tiles[item / heads];
-    const int r0 = a.pb.cu[ti.seq];
-    const int len = a.pb.cu[ti.seq + 1] - r0;
-    int nk = a.pb.seqused ? min(a.pb.seqused[ti.seq], len) : len;
-    nk = nk < 0 ? 0 : nk;
+    const TileItem ti = ti_next;
+    {
+      const int nxt = item + gridDim.x;
+      ti_next = a.pb.tiles[(nxt < n_items ? nxt : item) / heads];
+    }
+    const int r0 = ti.r0, len = ti.len, nk = ti.nk;
     const int krow = ti.row0 + 32 * wave + ln;      // this lane's key, within the sequence
     const bool wave_on = ti.row0 + 32 * wave < nk;  // wavefront owns at least one live key
     const bool tile_on = ti.row0 < nk;              // uniform over the workgroup

@@ -106,18 +106,34 @@ int check_ptr(const char* name, const void* ptr) {
   return FMHA_OK;
 }
 
-// Workgroups launched: one per (tile, head) that can exist.  max_seqlen, when
-// given, tightens the bound; the kernels stride over the list, so a bound
-// that is too small costs time, never correctness.
-unsigned grid_for(const fmha_varlen_params_t* p) {
+// Compute units of the current device (host query, cached per device).
+int compute_units() {
+  thread_local int cached_dev = -1, cached_cus = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (dev != cached_dev) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached_dev = dev;
+    cached_cus = n;
+  }
+  return cached_cus;
+}
+
+// Workgroups launched: persistent, `per_cu` per compute unit, but never more than
+// the (tile, head) items that can exist.  max_seqlen, when given, tightens that
+// bound; the kernels stride over the list, so a wrong bound costs time, never
+// correctness.
+unsigned grid_for(const fmha_varlen_params_t* p, int per_cu) {
   int64_t tiles = tile_capacity(p->batch, p->total_tokens);
   if (p->max_seqlen > 0) {
     const int64_t per_seq = (p->max_seqlen + fmha::kTileRows - 1) / fmha::kTileRows;
     if (per_seq * p->batch < tiles) tiles = per_seq * p->batch;
   }
   int64_t g = tiles * p->heads;
+  const int64_t resident = (int64_t)compute_units() * per_cu;
+  if (g > resident) g = resident;
   if (g < 1) g = 1;
-  if (g > (1 << 22)) g = 1 << 22;
   return (unsigned)g;
 }
 
@@ -132,8 +148,6 @@ int launch_schedule(const fmha_varlen_params_t* p, const Workspace& w, hipStream
 
 fmha::Problem problem_of(const fmha_varlen_params_t* p, const Workspace& w) {
   fmha::Problem pb;
-  pb.cu = p->cu_seqlens;
-  pb.seqused = p->seqused;
   pb.n_tiles = w.count;
   pb.tiles = w.list;
   pb.heads = p->heads;
@@ -189,7 +203,7 @@ int fmha_varlen_fwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   a.v = static_cast<const uint16_t*>(v);
   a.o = static_cast<uint16_t*>(o);
   a.lse = lse;
-  const unsigned grid = grid_for(p);
+  const unsigned grid = grid_for(p, 2);
   if (p->dtype == FMHA_F16)
     fmha::fmha_fwd_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
   else
@@ -238,7 +252,7 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   a.dq = static_cast<uint16_t*>(dq);
   a.dk = static_cast<uint16_t*>(dk);
   a.dv = static_cast<uint16_t*>(dv);
-  const unsigned grid = grid_for(p);
+  const unsigned grid = grid_for(p, 2);
   const bool run_dq = !(p->flags & FMHA_FLAG_BWD_ONLY_DKV);
   const bool run_dkv = !(p->flags & FMHA_FLAG_BWD_ONLY_DQ);
   if (p->dtype == FMHA_F16) {

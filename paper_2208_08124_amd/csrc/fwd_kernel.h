@@ -165,6 +165,8 @@ __device__ __forceinline__ void fwd_step(FwdAcc& acc, const f32x16 (&s_cur)[2], 
 template <typename T>
 __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) {
   __shared__ __align__(1024) uint16_t ring[kRing][2][kTileElems];  // [stage][K|V]
+  // The item's 128 query rows (two swizzled tiles): they arrive as whole 128-byte rows.
+  __shared__ __align__(1024) uint16_t xbuf[2][kTileElems];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -177,54 +179,50 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
   const RowRead rr(ln, g);
   const ColRead cr(lane);
   const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
+  const uint32_t xbuf_addr = lds_addr(&xbuf[0][0]);
   constexpr uint32_t kTileBytes = kTileElems * 2;
 
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const int head = item % heads;
-    const TileItem ti = a.pb.tiles[item / heads];
-    const int r0 = a.pb.cu[ti.seq];
-    const int len = a.pb.cu[ti.seq + 1] - r0;
-    int nk = a.pb.seqused ? min(a.pb.seqused[ti.seq], len) : len;
-    nk = nk < 0 ? 0 : nk;
-    const int qrow = ti.row0 + 32 * wave + ln;       // this lane's query, within the sequence
-    const bool wave_on = ti.row0 + 32 * wave < len;  // wavefront has at least one valid row
-    const uint16_t* kbase = a.k + (int64_t)r0 * a.k_stride + head * kHeadDim;
-    const uint16_t* vbase = a.v + (int64_t)r0 * a.v_stride + head * kHeadDim;
-    const int n = (nk + kBlockKeys - 1) / kBlockKeys;  // blocks of 64 keys
-
-    // Start moving block kt of K and V into ring stage `stage`: 4 pieces per thread.
-    const uint16_t* kpa = kbase + dl.row * a.k_stride + dl.chunk * 8;
-    const uint16_t* vpa = vbase + dl.row * a.v_stride + dl.chunk * 8;
-    auto start_block = [&](int kt, int stage) {
-      const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
-      if ((kt + 1) * kBlockKeys <= nk) {
-        const uint16_t* pk = kpa + (int64_t)kt * kBlockKeys * a.k_stride;
-        const uint16_t* pv = vpa + (int64_t)kt * kBlockKeys * a.v_stride;
-        dma_tile_full(pk, pk + 32 * a.k_stride, wave, st_addr);
-        dma_tile_full(pv, pv + 32 * a.v_stride, wave, st_addr + kTileBytes);
-      } else {
-        dma_tile(kbase, a.k_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr);
-        dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
-      }
-    };
+  // Start moving key block kt of a (sequence, head) into ring stage `stage`: 4 pieces per thread.
+  auto start_block = [&](const TileItem& t, int head, int kt, int stage) {
+    const uint16_t* kbase = a.k + (int64_t)t.r0 * a.k_stride + head * kHeadDim;
+    const uint16_t* vbase = a.v + (int64_t)t.r0 * a.v_stride + head * kHeadDim;
+    const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
+    if ((kt + 1) * kBlockKeys <= t.nk) {
+      const uint16_t* pk = kbase + (kt * kBlockKeys + dl.row) * a.k_stride + dl.chunk * 8;
+      const uint16_t* pv = vbase + (kt * kBlockKeys + dl.row) * a.v_stride + dl.chunk * 8;
+      dma_tile_full(pk, pk + 32 * a.k_stride, wave, st_addr);
+      dma_tile_full(pv, pv + 32 * a.v_stride, wave, st_addr + kTileBytes);
+    } else {
+      dma_tile(kbase, a.k_stride, kt * kBlockKeys, t.nk - 1, dl, wave, st_addr);
+      dma_tile(vbase, a.v_stride, kt * kBlockKeys, t.nk - 1, dl, wave, st_addr + kTileBytes);
+    }
+  };
+  // The first (up to) three key blocks of an item and its 128 query rows (clamped to the
+  // sequence; 4 pieces per thread, into xbuf); issued as soon as stages 0..2 and xbuf are
+  // free, i.e. before the previous item's outputs are written.
+  auto start_item = [&](const TileItem& t, int head) {
+    const int n = (t.nk + kBlockKeys - 1) / kBlockKeys;
 #pragma unroll
     for (int kt = 0; kt < kRing - 1; kt++)
-      if (kt < n) start_block(kt, kt);
+      if (kt < n) start_block(t, head, kt, kt);
+    const uint16_t* qbase = a.q + (int64_t)t.r0 * a.q_stride + head * kHeadDim;
+    dma_tile(qbase, a.q_stride, t.row0, t.len - 1, dl, wave, xbuf_addr);
+    dma_tile(qbase, a.q_stride, t.row0 + 64, t.len - 1, dl, wave, xbuf_addr + kTileBytes);
+  };
 
-    // Q^T as the B operand: column = query ln, slots = channels 16t + 8g .. +7.
-    // A negative scale is applied as a sign flip of Q so that the row maximum
-    // can be taken on the raw scores.
-    u32x4 qb[4];
-    {
-      const int qr = qrow < len ? qrow : len - 1;
-      const uint16_t* qp = a.q + (int64_t)(r0 + qr) * a.q_stride + head * kHeadDim + 8 * g;
-#pragma unroll
-      for (int t = 0; t < 4; t++) {
-        qb[t] = *reinterpret_cast<const u32x4*>(qp + 16 * t);
-#pragma unroll
-        for (int e = 0; e < 4; e++) qb[t][e] ^= qflip;
-      }
-    }
+  // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
+  // next item is fetched while the current one is computed.
+  TileItem ti_next = a.pb.tiles[(blockIdx.x < n_items ? blockIdx.x : 0) / heads];
+  if (blockIdx.x < n_items) start_item(ti_next, blockIdx.x % heads);
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const int head = item % heads;
+    const TileItem ti = ti_next;
+    const int item_next = item + gridDim.x;
+    ti_next = a.pb.tiles[(item_next < n_items ? item_next : item) / heads];
+    const int r0 = ti.r0, len = ti.len, nk = ti.nk;
+    const int qrow = ti.row0 + 32 * wave + ln;       // this lane's query, within the sequence
+    const bool wave_on = ti.row0 + 32 * wave < len;  // wavefront has at least one valid row
+    const int n = (nk + kBlockKeys - 1) / kBlockKeys;  // blocks of 64 keys
 
     FwdAcc acc;
 #pragma unroll
@@ -239,19 +237,26 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
     // landed (kt+1's keys are read in this step); block kt+3 is started into the stage
     // that block kt-1 occupied.  Each thread has 4 pieces per block in flight.
     static_assert(kRing == 4, "the waits below are written for a ring of four stages");
+    // everything in flight is this item's: first key blocks, queries (and the previous
+    // item's output rows on their way out)
+    wait_vmem<0>();
+    __syncthreads();
+    // Q^T as the B operand: column = query ln, slots = channels 16t + 8g .. +7.
+    // A negative scale is applied as a sign flip of Q so that the row maximum
+    // can be taken on the raw scores.
+    u32x4 qb[4];
+#pragma unroll
+    for (int t = 0; t < 4; t++) {
+      qb[t] = rr.read(xbuf[wave >> 1], wave & 1, t);
+#pragma unroll
+      for (int e = 0; e < 4; e++) qb[t][e] ^= qflip;
+    }
     if (n > 0) {
       f32x16 sA[2], sB[2];  // scores of even / odd blocks
-      if (n >= 3)
-        wait_vmem<8>();
-      else if (n == 2)
-        wait_vmem<4>();
-      else
-        wait_vmem<0>();
-      __syncthreads();
       if (wave_on) fwd_scores<T>(sA, &ring[0][0][0], qb, rr);
       auto step = [&](int kt, const f32x16 (&s_cur)[2], f32x16 (&s_next)[2]) {
         const int left = n - kt;  // blocks not yet soft-maxed, this one included
-        if (left >= 2) {          // block kt+1 has to be complete
+        if (left >= 2 && kt > 0) {  // block kt+1 has to be complete (at kt = 0 it already is)
           if (left >= 3)
             wait_vmem<4>();
           else
@@ -259,7 +264,7 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
           __syncthreads();  // also: everyone is done reading block kt-1's stage
         }
         const int stage = kt & 3;
-        if (kt + 3 < n) start_block(kt + 3, (stage + 3) & 3);
+        if (kt + 3 < n) start_block(ti, head, kt + 3, (stage + 3) & 3);
         if (wave_on) {
           const uint16_t* sV = &ring[0][0][0] + stage * (2 * kTileElems) + kTileElems;
           const uint16_t* sKn = &ring[0][0][0] + ((stage + 1) & 3) * (2 * kTileElems);
@@ -276,25 +281,35 @@ __global__ __launch_bounds__(kThreads, 2) void fmha_fwd_kernel(const FwdArgs a) 
         if (kt + 1 < n) step(kt + 1, sB, sA);
       }
     }
-    __syncthreads();  // the rings are free for the next item
+    __syncthreads();  // the ring and the query tiles are free
+    if (item_next < n_items) start_item(ti_next, item_next % heads);
 
-    // epilogue: combine the two half-rows' sums, normalise, store O and LSE
+    // epilogue: combine the two half-rows' sums, normalise; the output rows go through
+    // this wavefront's quarter of ring stage 3 (which the next item does not fill before
+    // its first barrier) so that they leave as whole 128-byte rows
     if (wave_on) {
       const float l_tot = acc.l_run + other_half(acc.l_run);
       const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-      if (qrow < len) {
-        uint16_t* op = a.o + (int64_t)(r0 + qrow) * a.o_stride + head * kHeadDim + 4 * g;
+      uint16_t* stage_o = &ring[kRing - 1][0][0] + wave * (32 * 64);
 #pragma unroll
-        for (int cb = 0; cb < 2; cb++)
+      for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-          for (int j = 0; j < 4; j++) {
-            u32x2 w = {Op<T>::pack2(acc.o[cb][4 * j] * inv, acc.o[cb][4 * j + 1] * inv),
-                       Op<T>::pack2(acc.o[cb][4 * j + 2] * inv, acc.o[cb][4 * j + 3] * inv)};
-            *reinterpret_cast<u32x2*>(op + 32 * cb + 8 * j) = w;
-          }
-        if (g == 0)
-          a.lse[(int64_t)head * a.pb.total_tokens + r0 + qrow] =
-              l_tot > 0.f ? (acc.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+        for (int j = 0; j < 4; j++) {
+          u32x2 w = {Op<T>::pack2(acc.o[cb][4 * j] * inv, acc.o[cb][4 * j + 1] * inv),
+                     Op<T>::pack2(acc.o[cb][4 * j + 2] * inv, acc.o[cb][4 * j + 3] * inv)};
+          *reinterpret_cast<u32x2*>(stage_o + tile_off(ln, 32 * cb + 8 * j + 4 * g)) = w;
+        }
+      if (qrow < len && g == 0)
+        a.lse[(int64_t)head * a.pb.total_tokens + r0 + qrow] =
+            l_tot > 0.f ? (acc.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+      const int orow0 = ti.row0 + 32 * wave;  // first row of this wavefront's piece
+#pragma unroll
+      for (int k4 = 0; k4 < 4; k4++) {
+        const int row = 8 * k4 + (lane >> 3);
+        const u32x4 w = *reinterpret_cast<const u32x4*>(stage_o + tile_off(row, 8 * (lane & 7)));
+        if (orow0 + row < len)
+          *reinterpret_cast<u32x4*>(a.o + (int64_t)(r0 + orow0 + row) * a.o_stride + head * kHeadDim +
+                                    8 * (lane & 7)) = w;
       }
     }
   }

@@ -9,14 +9,17 @@ constexpr int kTileRows = 128;  // rows (queries, or keys in the dK/dV pass) per
 constexpr int kBlockKeys = 64;  // rows staged in LDS per inner step
 constexpr int kThreads = 256;   // 4 wavefronts; each owns 32 rows of the tile
 
+// One unit of work: a tile of up to 128 rows of one sequence, with everything a
+// kernel needs to know about that sequence, so that starting a tile costs one
+// (prefetchable) 16-byte load instead of a chain of dependent ones.
 struct TileItem {
-  int32_t seq;   // sequence index
+  int32_t r0;    // packed row at which the sequence starts
+  int32_t len;   // rows of the sequence (queries)
+  int32_t nk;    // keys attended: len, or min(seqused, len)
   int32_t row0;  // first row of the tile within the sequence
 };
 
 struct Problem {
-  const int32_t* cu;       // [B+1]
-  const int32_t* seqused;  // [B] or null
   const int32_t* n_tiles;  // device scalar written by the schedule kernel
   const TileItem* tiles;   // tile list, longest sequences first
   int32_t heads;

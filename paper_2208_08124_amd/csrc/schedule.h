@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     const int nt = (len + kTileRows - 1) / kTileRows;
     int at = atomicAdd(&cursor[sched_bucket(nk)], nt);
     for (int t = 0; t < nt; t++)
-      if (at + t < cap) list[at + t] = TileItem{i, t * kTileRows};
+      if (at + t < cap) list[at + t] = TileItem{cu[i], len, nk < 0 ? 0 : nk, t * kTileRows};
   }
 }
 

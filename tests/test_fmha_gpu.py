@@ -104,11 +104,12 @@ def test_schedule_covers_every_tile_once_longest_first():
     cap, c_off, l_off = fmha.fmha_varlen_schedule_info(b["batch"], b["total_tokens"])
     ws = db.ws.cpu().numpy()
     n = int(ws[c_off:c_off + 4].view(np.int32)[0])
-    items = ws[l_off:l_off + 8 * n].view(np.int32).reshape(n, 2)
-    want = {(i, r) for i, L in enumerate(lengths) for r in range(0, L, 128)}
+    items = ws[l_off:l_off + 16 * n].view(np.int32).reshape(n, 4)   # (r0, len, nk, row0)
+    cu = b["cu_seqlens"]
+    want = {(int(cu[i]), int(L), int(L), r) for i, L in enumerate(lengths) for r in range(0, L, 128)}
     got = [tuple(x) for x in items.tolist()]
     assert n <= cap and len(got) == len(set(got)) and set(got) == want
-    bucket = np.minimum((lengths[items[:, 0]] + 7) // 8, 127)
+    bucket = np.minimum((items[:, 1] + 7) // 8, 127)
     assert (np.diff(bucket) <= 0).all(), "tiles are not ordered longest sequence first"
 
 
