@@ -33,66 +33,59 @@ static __device__ __forceinline__ u32x4 pack8(const float (&x)[16], int t2) {
 }
 
 // ---------------------------------------------------------------- pass 1: dQ
-// One block of 64 keys for one wavefront (32 queries).
+// One block of 64 keys for one wavefront (32 queries), done as two halves of 32 keys
+// so that only one half's scores and operands are live at a time.
 template <typename T, bool RAGGED>
 __device__ __forceinline__ void dq_block(f32x16 (&dq)[2], const uint16_t* sK, const uint16_t* sV,
                                          const u32x4 (&qb)[4], const u32x4 (&gb)[4], float c2,
                                          float lse2, float dsum, int key_base, int nk, int g,
                                          const RowRead& rr, const ColRead& cr) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  u32x4 ka[4][2], va[4][2];
 #pragma unroll
-  for (int t = 0; t < 4; t++)
+  for (int kb = 0; kb < 2; kb++) {
+    if (RAGGED && key_base + 32 * kb >= nk) break;
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 ka[4], va[4];
 #pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
-      ka[t][kb] = rr.read(sK, kb, t);
-      va[t][kb] = rr.read(sV, kb, t);
+    for (int t = 0; t < 4; t++) {
+      ka[t] = rr.read(sK, kb, t);
+      va[t] = rr.read(sV, kb, t);
     }
-  __builtin_amdgcn_sched_barrier(0);
-  // S^T = K Q^T, dP^T = V dO^T : rows = keys, column = query ln
-  f32x16 s[2], dp[2];
+    __builtin_amdgcn_sched_barrier(0);
+    f32x16 s, dp;
 #pragma unroll
-  for (int t = 0; t < 4; t++)
-#pragma unroll
-    for (int kb = 0; kb < 2; kb++) {
-      s[kb] = Op<T>::mfma(ka[t][kb], qb[t], t == 0 ? zero : s[kb]);
-      dp[kb] = Op<T>::mfma(va[t][kb], gb[t], t == 0 ? zero : dp[kb]);
+    for (int t = 0; t < 4; t++) {
+      s = Op<T>::mfma(ka[t], qb[t], t == 0 ? zero : s);
+      dp = Op<T>::mfma(va[t], gb[t], t == 0 ? zero : dp);
     }
-  __builtin_amdgcn_sched_barrier(0);
-  u32x4 kT[2][2][2];  // K^T operands: [key block][16-key step][channel block]
-#pragma unroll
-  for (int kb = 0; kb < 2; kb++)
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 kT[2][2];
 #pragma unroll
     for (int t2 = 0; t2 < 2; t2++)
 #pragma unroll
-      for (int cb = 0; cb < 2; cb++) kT[kb][t2][cb] = cr.read(sK, 2 * kb + t2, cb);
-  __builtin_amdgcn_sched_barrier(0);
-  const int key0 = key_base + 4 * g;
-  u32x4 dsb[2][2];  // dS^T as B operands
-#pragma unroll
-  for (int kb = 0; kb < 2; kb++) {
+      for (int cb = 0; cb < 2; cb++) kT[t2][cb] = cr.read(sK, 2 * kb + t2, cb);
+    __builtin_amdgcn_sched_barrier(0);
+    const int key0 = key_base + 32 * kb + 4 * g;
     float ds[16];
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-      float p = fast_exp2(__builtin_fmaf(s[kb][r], c2, -lse2));
-      if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) p = 0.f;
-      ds[r] = p * (dp[kb][r] - dsum);
+      float p = fast_exp2(__builtin_fmaf(s[r], c2, -lse2));
+      if (RAGGED && key0 + 8 * (r >> 2) + (r & 3) >= nk) p = 0.f;
+      ds[r] = p * (dp[r] - dsum);
     }
+    u32x4 dsb[2];
 #pragma unroll
-    for (int t2 = 0; t2 < 2; t2++) dsb[kb][t2] = pack8<T>(ds, t2);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  // dQ^T += K^T dS^T : rows = channels, contraction over keys
-#pragma unroll
-  for (int kb = 0; kb < 2; kb++)
+    for (int t2 = 0; t2 < 2; t2++) dsb[t2] = pack8<T>(ds, t2);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int t2 = 0; t2 < 2; t2++)
 #pragma unroll
-      for (int cb = 0; cb < 2; cb++) dq[cb] = Op<T>::mfma(kT[kb][t2][cb], dsb[kb][t2], dq[cb]);
+      for (int cb = 0; cb < 2; cb++) dq[cb] = Op<T>::mfma(kT[t2][cb], dsb[t2], dq[cb]);
+  }
 }
 
 template <typename T>
-__global__ __launch_bounds__(kThreads, 2) void bwd_dq_kernel(const BwdArgs a) {
+__global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
   __shared__ __align__(1024) uint16_t ring[kBwdStages][2][kTileElems];  // [stage][K|V]
 
   const int tid = threadIdx.x;

@@ -203,7 +203,7 @@ int fmha_varlen_fwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   a.v = static_cast<const uint16_t*>(v);
   a.o = static_cast<uint16_t*>(o);
   a.lse = lse;
-  const unsigned grid = grid_for(p, 2);
+  const unsigned grid = grid_for(p, 3);
   if (p->dtype == FMHA_F16)
     fmha::fmha_fwd_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
   else
@@ -252,14 +252,14 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   a.dq = static_cast<uint16_t*>(dq);
   a.dk = static_cast<uint16_t*>(dk);
   a.dv = static_cast<uint16_t*>(dv);
-  const unsigned grid = grid_for(p, 2);
+  const unsigned grid_dq = grid_for(p, 3), grid = grid_for(p, 2);
   const bool run_dq = !(p->flags & FMHA_FLAG_BWD_ONLY_DKV);
   const bool run_dkv = !(p->flags & FMHA_FLAG_BWD_ONLY_DQ);
   if (p->dtype == FMHA_F16) {
-    if (run_dq) fmha::bwd_dq_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
+    if (run_dq) fmha::bwd_dq_kernel<_Float16><<<grid_dq, fmha::kThreads, 0, st>>>(a);
     if (run_dkv) fmha::bwd_dkv_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
   } else {
-    if (run_dq) fmha::bwd_dq_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
+    if (run_dq) fmha::bwd_dq_kernel<__bf16><<<grid_dq, fmha::kThreads, 0, st>>>(a);
     if (run_dkv) fmha::bwd_dkv_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
   }
   hipError_t e = hipGetLastError();
