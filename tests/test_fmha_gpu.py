@@ -175,3 +175,83 @@ def test_error_codes_need_no_device_work():
         fmha.fmha_varlen_fwd(db.q, db.k, db.v, db.cu, 8, 0.125, db.o, db.lse, small)
     assert e.value.code == fmha.FMHA_ERR_WORKSPACE
     del bad
+
+
+def test_config5_full_size_bf16_sampled_against_oracle():
+    """2048 sequences, 12 heads, bf16, at the launch configuration the benchmark uses.
+    The oracle checks a sample of sequences one by one; sum rules check all of them."""
+    b = wl.make_workload(5)
+    db = DeviceBatch(b, True)
+    db.fwd(cu_seqlens_host=torch.from_numpy(b["cu_seqlens"]))
+    db.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    for t in (db.o, db.dq, db.dk, db.dv, db.lse):
+        assert not torch.isnan(t).any(), "rows left unwritten"
+    L, cu = b["lengths"], b["cu_seqlens"]
+    rng = np.random.default_rng(5)
+    pick = sorted({0, len(L) - 1, int(L.argmin()), int(L.argmax())} | set(rng.choice(len(L), 20, replace=False).tolist()))
+    rows = np.concatenate([np.arange(cu[i], cu[i + 1]) for i in pick])
+    sub = {n: wl.bits_to_f64(b[n][rows], "bf16") for n in ("q", "k", "v", "do")}
+    sub_cu = wl.cu_from_lengths(L[pick])
+    o_ref, _ = oracle.fwd(sub["q"], sub["k"], sub["v"], sub_cu, b["scale"])
+    g_ref = oracle.bwd(sub["q"], sub["k"], sub["v"], sub["do"], sub_cu, b["scale"])
+    ridx = torch.from_numpy(rows).cuda()
+    o = to_f64(db.o[ridx])
+    assert (np.abs(o - o_ref) <= O_TOL + ulp_half(o_ref, "bf16")).all()
+    for name, got, want in zip(("dq", "dk", "dv"), (db.dq, db.dk, db.dv), g_ref):
+        g = to_f64(got[ridx])
+        rel = np.abs(g - want).max() / max(np.abs(want).max(), G_FLOOR)
+        assert rel <= G_TOL, f"{name}: {rel:.3e}"
+    # properties that hold for every sequence: softmax rows sum to one => sum_j dV_j = sum_r dO_r,
+    # and dS rows sum to zero => sum_j dK_j = 0 (bf16 storage of 512 summands bounds the slack)
+    seq_id = torch.repeat_interleave(torch.arange(len(L), device="cuda"), torch.from_numpy(L).cuda().long())
+    def seg_sum(t):
+        out = torch.zeros((len(L),) + t.shape[1:], dtype=torch.float32, device="cuda")
+        return out.index_add_(0, seq_id, t.float())
+    dv_sum, do_sum, dk_sum = seg_sum(db.dv), seg_sum(db.do), seg_sum(db.dk)
+    assert (dv_sum - do_sum).abs().max().item() <= 0.02 * do_sum.abs().max().item()
+    assert dk_sum.abs().max().item() <= 0.02 * db.dk.float().abs().max().item() * 8
+
+
+def test_padded_equals_packed_at_config4_size():
+    b = wl.make_workload(4)
+    db = run(b, True)
+    p = wl.pad_batch(b, 512)
+    dp = DeviceBatch(p, True)
+    dp.fwd()
+    dp.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    rows = torch.from_numpy(wl.valid_row_index(b["lengths"], 512)).cuda()
+    for x, y in ((dp.o, db.o), (dp.dq, db.dq), (dp.dk, db.dk), (dp.dv, db.dv)):
+        assert torch.equal(x[rows], y)
+
+
+def test_degenerate_batches():
+    # no sequences / no tokens: nothing is launched, the call succeeds
+    q = torch.zeros((0, 2, 64), dtype=torch.float16, device="cuda")
+    one = torch.zeros((1, 2, 64), dtype=torch.float16, device="cuda")
+    lse = torch.zeros((2, 1), dtype=torch.float32, device="cuda")
+    ws = fmha.alloc_workspace(3, 0, 2, True)
+    cu0 = torch.zeros(4, dtype=torch.int32, device="cuda")
+    p, _ = fmha._params(one, cu0, 0, 0.125, ws, None, None, False)
+    p.total_tokens = 0
+    import ctypes
+    rc = fmha.lib().fmha_varlen_fwd(ctypes.byref(p), one.data_ptr(), one.data_ptr(), one.data_ptr(),
+                                    one.data_ptr(), lse.data_ptr(), None)
+    assert rc == fmha.FMHA_OK
+    del q
+    # a single token, and one sequence much longer than the tuned range
+    for lengths, heads in (([1], 1), ([4100], 1), ([0, 0, 5, 0], 2)):
+        b = wl.make_batch(lengths, heads, "f16", seed=len(lengths))
+        run(b, True)
+
+
+def test_two_runs_are_bit_identical():
+    b = wl.make_workload(4)
+    a_, b_ = DeviceBatch(b, True), DeviceBatch(b, True)
+    for d in (a_, b_):
+        d.fwd()
+        d.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    for x, y in ((a_.o, b_.o), (a_.lse, b_.lse), (a_.dq, b_.dq), (a_.dk, b_.dk), (a_.dv, b_.dv)):
+        assert torch.equal(x, y)
