@@ -24,6 +24,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # MI355X dense MFMA, published
 HBM_GBS = 8000.0
+# HBM bytes per launch on workload 3 from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs, scaled by
+# a plain-copy reference (factors 2.0 and 1.0); see profiles/fmha_kernels_bert_large_fwd_bwd.md
+MEASURED_TRAFFIC_CFG3 = {"fmha_fwd_kernel": 97.5e6 + 33.4e6, "bwd_dq_kernel": 172.9e6 + 37.8e6,
+                         "bwd_dkv_kernel": 132.4e6 + 64.7e6}
 
 
 def parse():
@@ -34,6 +38,9 @@ def parse():
     ap.add_argument("--config", type=int, default=3, help="workload 2..5 (3 = headline)")
     ap.add_argument("--uniform", type=str, default=None, metavar="L,B",
                     help="kernel study: B sequences of exactly L tokens instead of --config's lengths")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="only run a plain device-to-device copy of this many MiB a few times "
+                         "(reference reading for rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
     return ap.parse_args()
@@ -55,6 +62,15 @@ def main():
         sys.exit(1)
     fmha.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": n, "copies": 5}))
+        return
     dev_dt = {"f16": torch.float16, "bf16": torch.bfloat16}
 
     b = wl.make_workload(args.config, backward=True)
@@ -136,7 +152,8 @@ def main():
     ach = k_fl[dom] / (k_ms[dom] * 1e-3) / 1e12
     peak = PEAK_TFLOPS[dt]
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": peak,
-                "unit": "TFLOP/s", "frac": round(ach / peak, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(ach / peak, 4),
+                "traffic": MEASURED_TRAFFIC_CFG3[dom] if (args.config == 3 and not args.uniform) else None,
                 "avg_launch_ms": round(k_ms[dom], 5),
                 "kernels_ms": {k: round(v, 5) for k, v in k_ms.items()},
                 "kernels_tflops": {k: round(k_fl[k] / (k_ms[k] * 1e-3) / 1e12, 2) for k in k_ms},
