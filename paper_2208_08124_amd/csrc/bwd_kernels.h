@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
   const int wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 5, ln = lane & 31;
   const int heads = a.pb.heads;
-  const int n_items = *a.pb.n_tiles * heads;
+  const int n_items = tile_count(a.pb) * heads;
   const float c2 = a.pb.scale * kLog2e;
   const DmaLane dl(wave, lane);
   const RowRead rr(ln, g);
@@ -109,13 +109,13 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
-  TileItem ti_next = a.pb.tiles[(blockIdx.x < n_items ? blockIdx.x : 0) / heads];
+  TileItem ti_next = load_tile(a.pb, (blockIdx.x < n_items ? blockIdx.x : 0) / heads);
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
     const TileItem ti = ti_next;
     {
       const int nxt = item + gridDim.x;
-      ti_next = a.pb.tiles[(nxt < n_items ? nxt : item) / heads];
+      ti_next = load_tile(a.pb, (nxt < n_items ? nxt : item) / heads);
     }
     const int r0 = ti.r0, len = ti.len, nk = ti.nk;
     const int qrow = ti.row0 + 32 * wave + ln;
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
   const int wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 5, ln = lane & 31;
   const int heads = a.pb.heads;
-  const int n_items = *a.pb.n_tiles * heads;
+  const int n_items = tile_count(a.pb) * heads;
   const float c2 = a.pb.scale * kLog2e;
   const DmaLane dl(wave, lane);
   const RowRead rr(ln, g);
@@ -311,13 +311,13 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
-  TileItem ti_next = a.pb.tiles[(blockIdx.x < n_items ? blockIdx.x : 0) / heads];
+  TileItem ti_next = load_tile(a.pb, (blockIdx.x < n_items ? blockIdx.x : 0) / heads);
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
     const TileItem ti = ti_next;
     {
       const int nxt = item + gridDim.x;
-      ti_next = a.pb.tiles[(nxt < n_items ? nxt : item) / heads];
+      ti_next = load_tile(a.pb, (nxt < n_items ? nxt : item) / heads);
     }
     const int r0 = ti.r0, len = ti.len, nk = ti.nk;
     const int krow = ti.row0 + 32 * wave + ln;      // this lane's key, within the sequence

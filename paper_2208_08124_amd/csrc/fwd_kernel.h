@@ -126,6 +126,11 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
   acc.l_run += psum;
 }
 
+// Byte offset, within a ring stage and relative to the wavefront's first private
+// row, of the i-th (0..3) 1 KB piece that only that wavefront's fetches write:
+// rows 8w..8w+7 and 32+8w..32+8w+7 of the stage's first and second tile.
+__device__ __forceinline__ constexpr int own_piece(int i) { return (i >> 1) * 8192 + (i & 1) * 4096; }
+
 template <typename T>
 __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) {
   __shared__ __align__(1024) uint16_t ring[kFwdStages][2][kTileElems];  // [stage][K|V]
@@ -134,7 +139,7 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
   const int wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 5, ln = lane & 31;
   const int heads = a.pb.heads;
-  const int n_items = *a.pb.n_tiles * heads;
+  const int n_items = tile_count(a.pb) * heads;
   const float c2 = fabsf(a.pb.scale) * kLog2e;  // scores are kept in the log2 domain
   const uint32_t qflip = a.pb.scale < 0.f ? 0x80008000u : 0u;
   const DmaLane dl(wave, lane);
@@ -142,27 +147,29 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
   const ColRead cr(lane);
   const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
   constexpr uint32_t kTileBytes = kTileElems * 2;
+  // this lane's piece within a 64-row block (rows dl.row and dl.row + 32), in elements
+  const int k_lane = dl.row * (int)a.k_stride + dl.chunk * 8;
+  const int v_lane = dl.row * (int)a.v_stride + dl.chunk * 8;
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
-  TileItem ti_next = a.pb.tiles[(blockIdx.x < n_items ? blockIdx.x : 0) / heads];
+  TileItem ti_next = load_tile(a.pb, (blockIdx.x < n_items ? blockIdx.x : 0) / heads);
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
     const TileItem ti = ti_next;
     {
       const int nxt = item + gridDim.x;
-      ti_next = a.pb.tiles[(nxt < n_items ? nxt : item) / heads];
+      ti_next = load_tile(a.pb, (nxt < n_items ? nxt : item) / heads);
     }
     const int r0 = ti.r0, len = ti.len, nk = ti.nk;
-    const int qrow = ti.row0 + 32 * wave + ln;       // this lane's query, within the sequence
     const bool wave_on = ti.row0 + 32 * wave < len;  // wavefront has at least one valid row
     const uint16_t* kbase = a.k + (int64_t)r0 * a.k_stride + head * kHeadDim;
     const uint16_t* vbase = a.v + (int64_t)r0 * a.v_stride + head * kHeadDim;
     const int n = (nk + kBlockKeys - 1) / kBlockKeys;  // blocks of 64 keys
 
     // Start moving key block kt into ring stage `stage`: 4 pieces per thread.
-    const uint16_t* kpa = kbase + dl.row * a.k_stride + dl.chunk * 8;
-    const uint16_t* vpa = vbase + dl.row * a.v_stride + dl.chunk * 8;
+    const uint16_t* kpa = kbase + k_lane;
+    const uint16_t* vpa = vbase + v_lane;
     auto start_block = [&](int kt, int stage) {
       const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
       if ((kt + 1) * kBlockKeys <= nk) {
@@ -175,23 +182,23 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
         dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
       }
     };
-    if (n > 0) start_block(0, 0);
-    if (n > 1) start_block(1, 1);
-
-    // Q^T as the B operand: column = query ln, slots = channels 16t + 8g .. +7.
-    // A negative scale is applied as a sign flip of Q so that the row maximum
-    // can be taken on the raw scores.
-    u32x4 qb[4];
+    // Q first: each wavefront moves its own 32 query rows (four pieces of eight
+    // rows) into its private 4 KB of the last ring stage - the rows of that stage
+    // which only this wavefront's own fetches write, so no barrier is involved -
+    // ahead of the first two key blocks; they are awaited together with block 0.
+    const uint32_t own_addr = ring_addr + (kFwdStages - 1) * (2 * kTileBytes) + 1024u * wave;
     {
-      const int qr = qrow < len ? qrow : len - 1;
-      const uint16_t* qp = a.q + (int64_t)(r0 + qr) * a.q_stride + head * kHeadDim + 8 * g;
+      const uint16_t* qbase = a.q + (int64_t)r0 * a.q_stride + head * kHeadDim;
 #pragma unroll
-      for (int t = 0; t < 4; t++) {
-        qb[t] = *reinterpret_cast<const u32x4*>(qp + 16 * t);
-#pragma unroll
-        for (int e = 0; e < 4; e++) qb[t][e] ^= qflip;
+      for (int i = 0; i < 4; i++) {
+        const int r = 8 * i + (lane >> 3);  // row within the wavefront's 32
+        const int qr = min(ti.row0 + 32 * wave + r, len - 1);
+        dma16(qbase + (int64_t)qr * a.q_stride + ((lane & 7) ^ swz(r)) * 8,
+              __builtin_amdgcn_readfirstlane(own_addr + own_piece(i)));
       }
     }
+    if (n > 0) start_block(0, 0);
+    if (n > 1) start_block(1, 1);
 
     FwdAcc acc;
 #pragma unroll
@@ -200,6 +207,27 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
       for (int r = 0; r < 16; r++) acc.o[cb][r] = 0.f;
     acc.m_run = -INFINITY;
     acc.l_run = 0.f;
+
+    // Q and block 0 have landed once at most the 4 pieces of block 1 are outstanding
+    // (vector memory loads complete in issue order).
+    if (n > 1)
+      wait_vmem<4>();
+    else
+      wait_vmem<0>();
+    // Q^T as the B operand: column = query ln, slots = channels 16t + 8g .. +7.  A
+    // negative scale is applied as a sign flip of Q so that the row maximum can be
+    // taken on the raw scores.
+    u32x4 qb[4];
+    {
+      const uint16_t* sq = &ring[kFwdStages - 1][0][0] + 512 * wave + own_piece(ln >> 3) / 2 + (ln & 7) * 64;
+      const int sw = swz(ln);
+#pragma unroll
+      for (int t = 0; t < 4; t++) {
+        qb[t] = *reinterpret_cast<const u32x4*>(sq + (((2 * t + g) ^ sw) << 3));
+#pragma unroll
+        for (int e = 0; e < 4; e++) qb[t][e] ^= qflip;
+      }
+    }
 
     int stage = 0;  // kt % 3
     for (int kt = 0; kt < n; kt++) {
@@ -224,23 +252,40 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
     }
     __syncthreads();  // the ring is free for the next item
 
-    // epilogue: combine the two half-rows' sums, normalise, store O and LSE
+    // epilogue: combine the two half-rows' sums, normalise, store O and LSE.  O
+    // leaves as whole rows: each wavefront turns its 32 x 64 tile around in its
+    // private 4 KB of the last ring stage, so that a store instruction writes 8
+    // complete 128-byte rows instead of 16 bytes in each of 32 rows.
     if (wave_on) {
       const float l_tot = acc.l_run + other_half(acc.l_run);
       const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-      if (qrow < len) {
-        uint16_t* op = a.o + (int64_t)(r0 + qrow) * a.o_stride + head * kHeadDim + 4 * g;
+      // lane-derived addresses are recomputed here (all 64 lanes are active) rather
+      // than kept in registers through the key loop
+      const int le = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+      const int ge = le >> 5, lne = le & 31;
+      uint16_t* so = &ring[kFwdStages - 1][0][0] + 512 * wave;
+      const int sw = swz(lne);
+      uint16_t* sw_row = so + own_piece(lne >> 3) / 2 + (lne & 7) * 64 + 4 * ge;
 #pragma unroll
-        for (int cb = 0; cb < 2; cb++)
+      for (int cb = 0; cb < 2; cb++)
 #pragma unroll
-          for (int j = 0; j < 4; j++) {
-            u32x2 w = {Op<T>::pack2(acc.o[cb][4 * j] * inv, acc.o[cb][4 * j + 1] * inv),
-                       Op<T>::pack2(acc.o[cb][4 * j + 2] * inv, acc.o[cb][4 * j + 3] * inv)};
-            *reinterpret_cast<u32x2*>(op + 32 * cb + 8 * j) = w;
-          }
-        if (g == 0)
-          a.lse[(int64_t)head * a.pb.total_tokens + r0 + qrow] =
-              l_tot > 0.f ? (acc.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+        for (int j = 0; j < 4; j++) {
+          u32x2 w = {Op<T>::pack2(acc.o[cb][4 * j] * inv, acc.o[cb][4 * j + 1] * inv),
+                     Op<T>::pack2(acc.o[cb][4 * j + 2] * inv, acc.o[cb][4 * j + 3] * inv)};
+          *reinterpret_cast<u32x2*>(sw_row + (((4 * cb + j) ^ sw) << 3)) = w;
+        }
+      const int qrow = ti.row0 + 32 * wave + lne;  // this lane's query, within the sequence
+      if (qrow < len && ge == 0)
+        a.lse[(int64_t)head * a.pb.total_tokens + r0 + qrow] =
+            l_tot > 0.f ? (acc.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+      __builtin_amdgcn_wave_barrier();  // same wavefront: its LDS operations execute in order
+      const int chunk = le & 7;
+      uint16_t* op = a.o + (int64_t)(r0 + ti.row0 + 32 * wave) * a.o_stride + head * kHeadDim + 8 * chunk;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int row = 8 * i + (le >> 3);
+        const u32x4 w = *reinterpret_cast<const u32x4*>(so + own_piece(i) / 2 + (le >> 3) * 64 + ((chunk ^ swz(row)) << 3));
+        if (ti.row0 + 32 * wave + row < len) *reinterpret_cast<u32x4*>(op + (int64_t)row * a.o_stride) = w;
       }
     }
   }

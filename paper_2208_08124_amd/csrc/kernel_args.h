@@ -45,4 +45,18 @@ struct BwdArgs {
   int64_t q_stride, k_stride, v_stride, o_stride, do_stride, dq_stride, dk_stride, dv_stride;
 };
 
+#ifdef __HIPCC__
+// The tile list and its count were written by an earlier kernel and are only
+// read here.  Reading them through the constant address space lets the compiler
+// use scalar loads (wave-uniform, tracked by their own counter) instead of vector
+// loads, whose completion would otherwise be awaited together with - and so
+// serialise - whatever else the wavefront has in flight on the vector memory path.
+typedef const __attribute__((address_space(4))) int32_t* ConstInt;
+__device__ __forceinline__ TileItem load_tile(const Problem& pb, int i) {
+  ConstInt p = (ConstInt)(uintptr_t)(pb.tiles + i);
+  return TileItem{p[0], p[1], p[2], p[3]};
+}
+__device__ __forceinline__ int tile_count(const Problem& pb) { return *(ConstInt)(uintptr_t)pb.n_tiles; }
+#endif
+
 }  // namespace fmha

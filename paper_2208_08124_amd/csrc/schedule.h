@@ -30,7 +30,7 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   for (int i = tid; i < batch; i += kSchedThreads) {
     const int len = cu[i + 1] - cu[i];
     if (len <= 0) continue;
-    int nk = seqused ? min(seqused[i], len) : len;
+    const int nk = seqused ? min(max(seqused[i], 0), len) : len;
     atomicAdd(&cursor[sched_bucket(nk)], (len + kTileRows - 1) / kTileRows);
   }
   __syncthreads();
@@ -47,11 +47,11 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   for (int i = tid; i < batch; i += kSchedThreads) {
     const int len = cu[i + 1] - cu[i];
     if (len <= 0) continue;
-    int nk = seqused ? min(seqused[i], len) : len;
+    const int nk = seqused ? min(max(seqused[i], 0), len) : len;
     const int nt = (len + kTileRows - 1) / kTileRows;
     int at = atomicAdd(&cursor[sched_bucket(nk)], nt);
     for (int t = 0; t < nt; t++)
-      if (at + t < cap) list[at + t] = TileItem{cu[i], len, nk < 0 ? 0 : nk, t * kTileRows};
+      if (at + t < cap) list[at + t] = TileItem{cu[i], len, nk, t * kTileRows};
   }
 }
 
