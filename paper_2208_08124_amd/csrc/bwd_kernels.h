@@ -99,6 +99,9 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
   const ColRead cr(lane);
   const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
   constexpr uint32_t kTileBytes = kTileElems * 2;
+  // this lane's piece within a 64-row block (rows dl.row and dl.row + 32), in elements
+  const uint32_t k_lane = dl.row * (uint32_t)a.k_stride + dl.chunk * 8;
+  const uint32_t v_lane = dl.row * (uint32_t)a.v_stride + dl.chunk * 8;
 
   // one entry behind each statistics array stands for "row past the end" in pass 2:
   // LSE = +inf makes its probabilities vanish
@@ -125,8 +128,12 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
     const uint16_t* vbase = a.v + (int64_t)r0 * a.v_stride + head * kHeadDim;
     const int n = (nk + kBlockKeys - 1) / kBlockKeys;
 
-    const uint16_t* kpa = kbase + dl.row * a.k_stride + dl.chunk * 8;
-    const uint16_t* vpa = vbase + dl.row * a.v_stride + dl.chunk * 8;
+    // (the empty asm keeps the 64-bit sums from being formed ahead of the item loop
+    // and held in registers through it)
+    uint32_t kl = k_lane, vl = v_lane;
+    asm volatile("" : "+v"(kl), "+v"(vl));
+    const uint16_t* kpa = kbase + kl;
+    const uint16_t* vpa = vbase + vl;
     auto start_block = [&](int kt, int stage) {  // 4 pieces per thread
       const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
       if ((kt + 1) * kBlockKeys <= nk) {
@@ -139,22 +146,36 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
         dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
       }
     };
+    // Everything the tile needs first is requested in one batch, so that one memory
+    // round trip covers it: the wavefront's 32 query rows (into its private rows of
+    // the last ring stage, see own_piece), the first two key blocks, then dO, O and
+    // LSE of this lane's query as ordinary loads.
+    {
+      const uint32_t own_addr = ring_addr + (kBwdStages - 1) * (2 * kTileBytes) + 1024u * wave;
+      const uint16_t* qbase = a.q + (int64_t)r0 * a.q_stride + head * kHeadDim;
+      const int le = lane_id();
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int r = 8 * i + (le >> 3);  // row within the wavefront's 32
+        const int qr = min(ti.row0 + 32 * wave + r, len - 1);
+        dma16(qbase + (int64_t)qr * a.q_stride + ((le & 7) ^ swz(r)) * 8,
+              __builtin_amdgcn_readfirstlane(own_addr + own_piece(i)));
+      }
+    }
     if (n > 0) start_block(0, 0);
     if (n > 1) start_block(1, 1);
 
-    // Q^T and dO^T as B operands (column = query ln, slots = channels 16t+8g..+7),
-    // and D = sum_c dO*O over this lane's 32 channels, completed with the other half.
+    // dO^T as B operand (column = query ln, slots = channels 16t+8g..+7), and
+    // D = sum_c dO*O over this lane's 32 channels, completed with the other half.
     u32x4 qb[4], gb[4];
     float dsum = 0.f, lse2 = 0.f;
     {
       const int qr = row_on ? qrow : len - 1;
       const int64_t tok = r0 + qr;
-      const uint16_t* qp = a.q + tok * a.q_stride + head * kHeadDim + 8 * g;
       const uint16_t* gp = a.d_o + tok * a.do_stride + head * kHeadDim + 8 * g;
       const uint16_t* op = a.o + tok * a.o_stride + head * kHeadDim + 8 * g;
 #pragma unroll
       for (int t = 0; t < 4; t++) {
-        qb[t] = *reinterpret_cast<const u32x4*>(qp + 16 * t);
         gb[t] = *reinterpret_cast<const u32x4*>(gp + 16 * t);
         const u32x4 ov = *reinterpret_cast<const u32x4*>(op + 16 * t);
 #pragma unroll
@@ -164,10 +185,16 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
       dsum += other_half(dsum);
       const int64_t si = (int64_t)head * a.pb.total_tokens + tok;
       lse2 = a.lse[si] * kLog2e;
-      if (row_on && g == 0) {
-        a.dsum[si] = dsum;
-        a.lse2[si] = lse2;
-      }
+    }
+    // Q^T as B operand, from the private rows.  The query rows were requested before
+    // the loads just consumed, so they have landed (vector memory loads complete in
+    // issue order); the explicit wait keeps the LDS reads below it.
+    wait_vmem<0>();
+    {
+      const uint16_t* sq = &ring[kBwdStages - 1][0][0] + 512 * wave + own_piece(ln >> 3) / 2 + (ln & 7) * 64;
+      const int sw = swz(ln);
+#pragma unroll
+      for (int t = 0; t < 4; t++) qb[t] = *reinterpret_cast<const u32x4*>(sq + (((2 * t + g) ^ sw) << 3));
     }
 
     f32x16 dq[2];  // dQ^T: column = query ln, rows = channels
@@ -198,18 +225,24 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
     }
     __syncthreads();  // the ring is free for the next item
 
-    if (row_on) {
-      const float sc = a.pb.scale;
-      uint16_t* op = a.dq + (int64_t)(r0 + qrow) * a.dq_stride + head * kHeadDim + 4 * g;
-#pragma unroll
-      for (int cb = 0; cb < 2; cb++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-          u32x2 w = {Op<T>::pack2(dq[cb][4 * j] * sc, dq[cb][4 * j + 1] * sc),
-                     Op<T>::pack2(dq[cb][4 * j + 2] * sc, dq[cb][4 * j + 3] * sc)};
-          *reinterpret_cast<u32x2*>(op + 32 * cb + 8 * j) = w;
-        }
+    // The row statistics for pass 2 are stored here rather than where they are
+    // computed: a store issued ahead of the key loop would have to be acknowledged
+    // before the loop's first wait on the fetch counter lets go.
+    {
+      const int le = lane_id();
+      const int row = ti.row0 + 32 * wave + (le & 31);
+      if (row < len && le < 32) {
+        const int64_t si = (int64_t)head * a.pb.total_tokens + r0 + row;
+        a.dsum[si] = dsum;
+        a.lse2[si] = lse2;
+      }
     }
+    // dQ leaves as whole rows, turned around in the wavefront's private rows of
+    // the last ring stage (see store_rows).
+    if (wave_on)
+      store_rows<T>(dq, a.pb.scale, &ring[kBwdStages - 1][0][0], wave,
+                    a.dq + (int64_t)(r0 + ti.row0 + 32 * wave) * a.dq_stride + head * kHeadDim, a.dq_stride,
+                    len - (ti.row0 + 32 * wave));
   }
 }
 
@@ -308,6 +341,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
   const ColRead cr(lane);
   const uint32_t ring_addr = lds_addr(&ring[0]);
   constexpr uint32_t kStageBytes = sizeof(DkvStage), kTileBytes = kTileElems * 2;
+  // this lane's piece within a 64-row block (rows dl.row and dl.row + 32), in elements
+  const uint32_t q_lane = dl.row * (uint32_t)a.q_stride + dl.chunk * 8;
+  const uint32_t g_lane = dl.row * (uint32_t)a.do_stride + dl.chunk * 8;
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
@@ -334,8 +370,12 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
     const float* stat_pad = stat_arr + (int64_t)heads * a.pb.total_tokens;
     const int n = tile_on ? (len + kBlockKeys - 1) / kBlockKeys : 0;  // query blocks
 
-    const uint16_t* qpa = qbase + dl.row * a.q_stride + dl.chunk * 8;
-    const uint16_t* gpa = gbase + dl.row * a.do_stride + dl.chunk * 8;
+    // (the empty asm keeps the 64-bit sums from being formed ahead of the item loop
+    // and held in registers through it)
+    uint32_t ql = q_lane, gl = g_lane;
+    asm volatile("" : "+v"(ql), "+v"(gl));
+    const uint16_t* qpa = qbase + ql;
+    const uint16_t* gpa = gbase + gl;
     auto start_block = [&](int qt, int stage) {  // 5 pieces per thread
       const uint32_t st_addr = ring_addr + stage * kStageBytes;
       if ((qt + 1) * kBlockKeys <= len) {
@@ -365,6 +405,12 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
         kb4[t] = *reinterpret_cast<const u32x4*>(kp + 16 * t);
         vb4[t] = *reinterpret_cast<const u32x4*>(vp + 16 * t);
       }
+      // Consume them here: the compiler then waits for these loads now, together
+      // with the first blocks, instead of in front of their first use inside the
+      // query loop - where the wait would also cover the block just requested and
+      // so expose a full memory round trip in every iteration.
+#pragma unroll
+      for (int t = 0; t < 4; t++) asm volatile("" ::"v"(kb4[t]), "v"(vb4[t]));
     }
 
     f32x16 dk[2], dv[2];  // dK^T, dV^T: column = key ln, rows = channels
@@ -392,29 +438,21 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
     __syncthreads();
 
     // every row of the tile is written: live keys get their gradients, keys
-    // masked by seqused get zeros
-    if (krow < len) {
-      const float sc = key_on ? a.pb.scale : 0.f;
+    // masked by seqused get zeros.  dK and dV leave as whole rows, turned around in
+    // the wavefront's private rows of the last two ring stages (see store_rows).
+    if (ti.row0 + 32 * wave < len) {
       if (!key_on) {
 #pragma unroll
         for (int cb = 0; cb < 2; cb++)
 #pragma unroll
           for (int r = 0; r < 16; r++) dv[cb][r] = dk[cb][r] = 0.f;
       }
-      const int64_t tok = r0 + krow;
-      uint16_t* kp = a.dk + tok * a.dk_stride + head * kHeadDim + 4 * g;
-      uint16_t* vp = a.dv + tok * a.dv_stride + head * kHeadDim + 4 * g;
-#pragma unroll
-      for (int cb = 0; cb < 2; cb++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-          u32x2 wk = {Op<T>::pack2(dk[cb][4 * j] * sc, dk[cb][4 * j + 1] * sc),
-                      Op<T>::pack2(dk[cb][4 * j + 2] * sc, dk[cb][4 * j + 3] * sc)};
-          u32x2 wv = {Op<T>::pack2(dv[cb][4 * j], dv[cb][4 * j + 1]),
-                      Op<T>::pack2(dv[cb][4 * j + 2], dv[cb][4 * j + 3])};
-          *reinterpret_cast<u32x2*>(kp + 32 * cb + 8 * j) = wk;
-          *reinterpret_cast<u32x2*>(vp + 32 * cb + 8 * j) = wv;
-        }
+      const int64_t tok = r0 + ti.row0 + 32 * wave;
+      const int n_rows = len - (ti.row0 + 32 * wave);
+      store_rows<T>(dk, a.pb.scale, ring[kBwdStages - 1].q, wave, a.dk + tok * a.dk_stride + head * kHeadDim,
+                    a.dk_stride, n_rows);
+      store_rows<T>(dv, 1.f, ring[kBwdStages - 2].q, wave, a.dv + tok * a.dv_stride + head * kHeadDim,
+                    a.dv_stride, n_rows);
     }
   }
 }

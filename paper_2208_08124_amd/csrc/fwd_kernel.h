@@ -126,11 +126,6 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
   acc.l_run += psum;
 }
 
-// Byte offset, within a ring stage and relative to the wavefront's first private
-// row, of the i-th (0..3) 1 KB piece that only that wavefront's fetches write:
-// rows 8w..8w+7 and 32+8w..32+8w+7 of the stage's first and second tile.
-__device__ __forceinline__ constexpr int own_piece(int i) { return (i >> 1) * 8192 + (i & 1) * 4096; }
-
 template <typename T>
 __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) {
   __shared__ __align__(1024) uint16_t ring[kFwdStages][2][kTileElems];  // [stage][K|V]
@@ -148,8 +143,8 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
   const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
   constexpr uint32_t kTileBytes = kTileElems * 2;
   // this lane's piece within a 64-row block (rows dl.row and dl.row + 32), in elements
-  const int k_lane = dl.row * (int)a.k_stride + dl.chunk * 8;
-  const int v_lane = dl.row * (int)a.v_stride + dl.chunk * 8;
+  const uint32_t k_lane = dl.row * (uint32_t)a.k_stride + dl.chunk * 8;
+  const uint32_t v_lane = dl.row * (uint32_t)a.v_stride + dl.chunk * 8;
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
@@ -168,8 +163,12 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
     const int n = (nk + kBlockKeys - 1) / kBlockKeys;  // blocks of 64 keys
 
     // Start moving key block kt into ring stage `stage`: 4 pieces per thread.
-    const uint16_t* kpa = kbase + k_lane;
-    const uint16_t* vpa = vbase + v_lane;
+    // (the empty asm keeps the 64-bit sums from being formed ahead of the item loop
+    // and held in registers through it)
+    uint32_t kl = k_lane, vl = v_lane;
+    asm volatile("" : "+v"(kl), "+v"(vl));
+    const uint16_t* kpa = kbase + kl;
+    const uint16_t* vpa = vbase + vl;
     auto start_block = [&](int kt, int stage) {
       const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
       if ((kt + 1) * kBlockKeys <= nk) {
@@ -189,11 +188,12 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
     const uint32_t own_addr = ring_addr + (kFwdStages - 1) * (2 * kTileBytes) + 1024u * wave;
     {
       const uint16_t* qbase = a.q + (int64_t)r0 * a.q_stride + head * kHeadDim;
+      const int le = lane_id();
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        const int r = 8 * i + (lane >> 3);  // row within the wavefront's 32
+        const int r = 8 * i + (le >> 3);  // row within the wavefront's 32
         const int qr = min(ti.row0 + 32 * wave + r, len - 1);
-        dma16(qbase + (int64_t)qr * a.q_stride + ((lane & 7) ^ swz(r)) * 8,
+        dma16(qbase + (int64_t)qr * a.q_stride + ((le & 7) ^ swz(r)) * 8,
               __builtin_amdgcn_readfirstlane(own_addr + own_piece(i)));
       }
     }
@@ -252,41 +252,19 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
     }
     __syncthreads();  // the ring is free for the next item
 
-    // epilogue: combine the two half-rows' sums, normalise, store O and LSE.  O
-    // leaves as whole rows: each wavefront turns its 32 x 64 tile around in its
-    // private 4 KB of the last ring stage, so that a store instruction writes 8
-    // complete 128-byte rows instead of 16 bytes in each of 32 rows.
+    // epilogue: combine the two half-rows' sums, normalise, store LSE and O (as
+    // whole rows, turned around in the wavefront's private rows of the last stage)
     if (wave_on) {
       const float l_tot = acc.l_run + other_half(acc.l_run);
       const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-      // lane-derived addresses are recomputed here (all 64 lanes are active) rather
-      // than kept in registers through the key loop
-      const int le = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-      const int ge = le >> 5, lne = le & 31;
-      uint16_t* so = &ring[kFwdStages - 1][0][0] + 512 * wave;
-      const int sw = swz(lne);
-      uint16_t* sw_row = so + own_piece(lne >> 3) / 2 + (lne & 7) * 64 + 4 * ge;
-#pragma unroll
-      for (int cb = 0; cb < 2; cb++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-          u32x2 w = {Op<T>::pack2(acc.o[cb][4 * j] * inv, acc.o[cb][4 * j + 1] * inv),
-                     Op<T>::pack2(acc.o[cb][4 * j + 2] * inv, acc.o[cb][4 * j + 3] * inv)};
-          *reinterpret_cast<u32x2*>(sw_row + (((4 * cb + j) ^ sw) << 3)) = w;
-        }
-      const int qrow = ti.row0 + 32 * wave + lne;  // this lane's query, within the sequence
-      if (qrow < len && ge == 0)
+      const int le = lane_id();
+      const int qrow = ti.row0 + 32 * wave + (le & 31);  // this lane's query, within the sequence
+      if (qrow < len && le < 32)
         a.lse[(int64_t)head * a.pb.total_tokens + r0 + qrow] =
             l_tot > 0.f ? (acc.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-      __builtin_amdgcn_wave_barrier();  // same wavefront: its LDS operations execute in order
-      const int chunk = le & 7;
-      uint16_t* op = a.o + (int64_t)(r0 + ti.row0 + 32 * wave) * a.o_stride + head * kHeadDim + 8 * chunk;
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        const int row = 8 * i + (le >> 3);
-        const u32x4 w = *reinterpret_cast<const u32x4*>(so + own_piece(i) / 2 + (le >> 3) * 64 + ((chunk ^ swz(row)) << 3));
-        if (ti.row0 + 32 * wave + row < len) *reinterpret_cast<u32x4*>(op + (int64_t)row * a.o_stride) = w;
-      }
+      store_rows<T>(acc.o, inv, &ring[kFwdStages - 1][0][0], wave,
+                    a.o + (int64_t)(r0 + ti.row0 + 32 * wave) * a.o_stride + head * kHeadDim, a.o_stride,
+                    len - (ti.row0 + 32 * wave));
     }
   }
 }

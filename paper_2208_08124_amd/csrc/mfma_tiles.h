@@ -230,4 +230,64 @@ static __device__ __forceinline__ void dma_tile(const uint16_t* base, int64_t st
   dma16(base + rb * stride + dl.chunk * 8, m0 + 4096u);
 }
 
+// ---------------------------------------------------------------------------
+// Rows of a ring stage that belong to one wavefront: with the piece assignment of
+// DmaLane, wavefront w is the only one whose fetches write rows 8w..8w+7 and
+// 32+8w..32+8w+7 of each of the stage's two tiles - four pieces of 1 KB.  Between
+// the end of one work item and the first fetch the same wavefront issues into
+// that stage for the next one, those 4 KB are scratch space that needs no
+// barrier.  own_piece(i) is the byte offset of piece i from the wavefront's first
+// private row (stage base + 1024 * w); `second_tile` is the byte distance between
+// the stage's two tiles.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ constexpr int own_piece(int i, int second_tile = 8192) {
+  return (i >> 1) * second_tile + (i & 1) * 4096;
+}
+
+// Lane number, recomputed from the execution mask (all 64 lanes active): two
+// instructions where it is needed beat a register - and everything the compiler
+// would derive from it ahead of time - held through the hot loop.  Volatile, so
+// that it stays where it is written.
+__device__ __forceinline__ int lane_id() {
+  int x;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(x));
+  return x;
+}
+
+// A wavefront's 32 x 64 result tile, held transposed in MFMA layout (x[cb][r] =
+// channel 32cb + 8(r/4) + 4g + r%4 of row ln), scaled, rounded to T and written to
+// global memory as whole 128-byte rows: the tile is turned around in the
+// wavefront's private pieces of `stage` (piece r/8 holds rows 8(r/8)..+7, 16-byte
+// chunk c of row r at position c ^ swz(r)), so that each store instruction covers
+// 8 complete rows instead of 16 bytes in each of 32.  `out` points at row 0 of the
+// tile, rows >= n_rows are not stored.  All 64 lanes must be active.
+template <typename T>
+__device__ __forceinline__ void store_rows(const f32x16 (&x)[2], float scale, uint16_t* stage, int wave,
+                                           uint16_t* out, int64_t out_stride, int n_rows,
+                                           int second_tile = 8192) {
+  // lane-derived addresses are computed here rather than kept in registers by the caller
+  const int lane = lane_id();
+  const int g = lane >> 5, ln = lane & 31;
+  uint16_t* so = stage + 512 * wave;
+  uint16_t* wr = so + own_piece(ln >> 3, second_tile) / 2 + (ln & 7) * 64 + 4 * g;
+  const int sw = swz(ln);
+#pragma unroll
+  for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      u32x2 w = {Op<T>::pack2(x[cb][4 * j] * scale, x[cb][4 * j + 1] * scale),
+                 Op<T>::pack2(x[cb][4 * j + 2] * scale, x[cb][4 * j + 3] * scale)};
+      *reinterpret_cast<u32x2*>(wr + (((4 * cb + j) ^ sw) << 3)) = w;
+    }
+  __builtin_amdgcn_wave_barrier();  // same wavefront: its LDS operations execute in order
+  const int chunk = lane & 7;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int row = 8 * i + (lane >> 3);
+    const u32x4 w = *reinterpret_cast<const u32x4*>(so + own_piece(i, second_tile) / 2 + (lane >> 3) * 64 +
+                                                    ((chunk ^ swz(row)) << 3));
+    if (row < n_rows) *reinterpret_cast<u32x4*>(out + (int64_t)row * out_stride + 8 * chunk) = w;
+  }
+}
+
 }  // namespace fmha
