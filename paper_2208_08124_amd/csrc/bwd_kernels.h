@@ -94,6 +94,7 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
   const int heads = a.pb.heads;
   const int n_items = tile_count(a.pb) * heads;
   const float c2 = a.pb.scale * kLog2e;
+  const int slot = blockIdx.x / max(gridDim.x / 3u, 1u);  // which of the 3 workgroups per compute unit
   const DmaLane dl(wave, lane);
   const RowRead rr(ln, g);
   const ColRead cr(lane);
@@ -211,6 +212,7 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
       else
         wait_vmem<0>();
       __syncthreads();  // everyone's pieces; and everyone is done with block kt-1's stage
+      rotate_priority(kt, slot, 3);
       const int ahead = stage == 0 ? kBwdStages - 1 : stage - 1;  // (kt + 2) % 3
       if (kt + 2 < n) start_block(kt + 2, ahead);
       if (wave_on) {
@@ -336,6 +338,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
   const int heads = a.pb.heads;
   const int n_items = tile_count(a.pb) * heads;
   const float c2 = a.pb.scale * kLog2e;
+  const int slot = blockIdx.x / max(gridDim.x / 2u, 1u);  // which of the 2 workgroups per compute unit
   const DmaLane dl(wave, lane);
   const RowRead rr(ln, g);
   const ColRead cr(lane);
@@ -426,6 +429,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
       else
         wait_vmem<0>();
       __syncthreads();
+      rotate_priority(qt, slot, 2);
       const int ahead = stage == 0 ? kBwdStages - 1 : stage - 1;
       if (qt + 2 < n) start_block(qt + 2, ahead);
       if (wave_on) {

