@@ -26,8 +26,8 @@ PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # MI355X dense MFMA, published
 HBM_GBS = 8000.0
 # HBM bytes per launch on workload 3 from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs, scaled by
 # a plain-copy reference (factors 2.0 and 1.0); see profiles/fmha_kernels_bert_large_fwd_bwd.md
-MEASURED_TRAFFIC_CFG3 = {"fmha_fwd_kernel": 97.5e6 + 33.4e6, "bwd_dq_kernel": 172.9e6 + 37.8e6,
-                         "bwd_dkv_kernel": 132.4e6 + 64.7e6}
+MEASURED_TRAFFIC_CFG3 = {"fmha_fwd_kernel": 97.3e6 + 33.3e6, "bwd_dq_kernel": 163.4e6 + 34.4e6,
+                         "bwd_dkv_kernel": 132.3e6 + 64.6e6}
 
 
 def parse():

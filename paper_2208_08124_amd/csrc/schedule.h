@@ -34,14 +34,29 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
     atomicAdd(&cursor[sched_bucket(nk)], (len + kTileRows - 1) / kTileRows);
   }
   __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int b = 0; b < kSchedBuckets; b++) {
-      int n = cursor[b];
-      cursor[b] = run;
-      run += n;
+  // exclusive prefix sum over the 128 buckets: two wavefronts scan 64 each, the
+  // second then adds the first one's total
+  __shared__ int half_total;
+  int incl = 0, mine = 0;
+  if (tid < kSchedBuckets) {
+    const int lane = tid & 63;
+    mine = cursor[tid];
+    incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
     }
-    *count = run < cap ? run : cap;
+    if (tid == 63) half_total = incl;
+  }
+  __syncthreads();
+  if (tid < kSchedBuckets) {
+    const int excl = incl - mine + (tid >= 64 ? half_total : 0);
+    cursor[tid] = excl;
+    if (tid == kSchedBuckets - 1) {
+      const int run = excl + mine;
+      *count = run < cap ? run : cap;
+    }
   }
   __syncthreads();
   for (int i = tid; i < batch; i += kSchedThreads) {
