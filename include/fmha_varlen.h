@@ -85,7 +85,9 @@ typedef struct fmha_varlen_params {
   const int32_t* cu_seqlens_host; /* optional host copy: lets the call validate the prefix sums */
   const int32_t* seqused;         /* optional device, B entries: only keys j < seqused[i] of
                                      sequence i are attended (padded layout with a key mask);
-                                     NULL = all L_i keys.  All L_i query rows are computed. */
+                                     NULL = all L_i keys.  Values are clamped to [0, L_i]; with no
+                                     key attended the rows get O = 0, LSE = -inf and zero
+                                     gradients.  All L_i query rows are computed. */
   void* workspace;                /* device, 256-byte aligned, see fmha_varlen_workspace_size */
   size_t workspace_bytes;
 } fmha_varlen_params_t;

@@ -27,10 +27,19 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   const int tid = threadIdx.x;
   if (tid < kSchedBuckets) cursor[tid] = 0;
   __syncthreads();
+  // The thread's first sequence stays in registers for the second sweep (one memory
+  // round trip less on the usual batch of at most 1024 sequences).
+  int r0_first = 0, len_first = 0, nk_first = 0;
   for (int i = tid; i < batch; i += kSchedThreads) {
-    const int len = cu[i + 1] - cu[i];
+    const int r0 = cu[i];
+    const int len = cu[i + 1] - r0;
+    const int nk = len <= 0 ? 0 : (seqused ? min(max(seqused[i], 0), len) : len);
+    if (i == tid) {
+      r0_first = r0;
+      len_first = len;
+      nk_first = nk;
+    }
     if (len <= 0) continue;
-    const int nk = seqused ? min(max(seqused[i], 0), len) : len;
     atomicAdd(&cursor[sched_bucket(nk)], (len + kTileRows - 1) / kTileRows);
   }
   __syncthreads();
@@ -60,13 +69,17 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   }
   __syncthreads();
   for (int i = tid; i < batch; i += kSchedThreads) {
-    const int len = cu[i + 1] - cu[i];
+    int r0 = r0_first, len = len_first, nk = nk_first;
+    if (i != tid) {
+      r0 = cu[i];
+      len = cu[i + 1] - r0;
+      nk = len <= 0 ? 0 : (seqused ? min(max(seqused[i], 0), len) : len);
+    }
     if (len <= 0) continue;
-    const int nk = seqused ? min(max(seqused[i], 0), len) : len;
     const int nt = (len + kTileRows - 1) / kTileRows;
     int at = atomicAdd(&cursor[sched_bucket(nk)], nt);
     for (int t = 0; t < nt; t++)
-      if (at + t < cap) list[at + t] = TileItem{cu[i], len, nk, t * kTileRows};
+      if (at + t < cap) list[at + t] = TileItem{r0, len, nk, t * kTileRows};
   }
 }
 

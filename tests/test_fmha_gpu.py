@@ -145,6 +145,37 @@ def test_strided_interleaved_qkv_and_determinism():
         assert torch.equal(x, y)
 
 
+def test_strided_outputs_leave_the_gaps_untouched():
+    # O, dQ, dK, dV each live in slot 0 of a [T, 2, H, 64] buffer (token stride 2*H*64);
+    # rows are written as whole 128-byte rows, slot 1 must keep its fill pattern
+    b = wl.make_batch([130, 7, 64, 200], 3, "bf16", seed=31)
+    ref = run(b, True)
+    d = DeviceBatch(b, True)
+    bufs = [torch.full((b["total_tokens"], 2, b["heads"], 64), 7.0, dtype=d.q.dtype, device="cuda") for _ in range(4)]
+    d.o, d.dq, d.dk, d.dv = (x[:, 0] for x in bufs)
+    d.fwd()
+    d.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    for got, want in ((d.o, ref.o), (d.dq, ref.dq), (d.dk, ref.dk), (d.dv, ref.dv)):
+        assert torch.equal(got, want)
+    for x in bufs:
+        assert bool((x[:, 1] == 7.0).all())
+
+
+def test_seqused_zero_negative_and_partial():
+    # keys attended per sequence: none, a negative count (treated as none), some, all
+    b = wl.make_batch([70, 40, 150, 33], 2, "f16", seed=41)
+    b["seqused"] = np.array([0, -3, 65, 33], dtype=np.int32)
+    db = run(b, True)
+    t0, t1 = 0, 70 + 40
+    assert not db.o[t0:t1].any() and bool(torch.isinf(db.lse[:, t0:t1]).all())
+    for g in (db.dq, db.dk, db.dv):
+        assert not g[t0:t1].any()
+    # keys beyond seqused get no gradient
+    k0 = 110 + 65
+    assert not db.dk[k0:110 + 150].any() and not db.dv[k0:110 + 150].any()
+
+
 def test_stream_order_without_host_sync():
     """Producer -> attention -> consumer on a side stream, no host waits in between."""
     b = wl.make_batch([300, 45], 2, "f16", seed=31, backward=False)
