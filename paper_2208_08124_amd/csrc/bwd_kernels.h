@@ -180,8 +180,7 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
         gb[t] = *reinterpret_cast<const u32x4*>(gp + 16 * t);
         const u32x4 ov = *reinterpret_cast<const u32x4*>(op + 16 * t);
 #pragma unroll
-        for (int e = 0; e < 4; e++)
-          dsum += Op<T>::lo(gb[t][e]) * Op<T>::lo(ov[e]) + Op<T>::hi(gb[t][e]) * Op<T>::hi(ov[e]);
+        for (int e = 0; e < 4; e++) dsum = Op<T>::dot2(gb[t][e], ov[e], dsum);
       }
       dsum += other_half(dsum);
       const int64_t si = (int64_t)head * a.pb.total_tokens + tok;

@@ -48,13 +48,10 @@ struct Op<_Float16> {
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, w), h2{(_Float16)1.f, (_Float16)1.f}, acc,
                                   false);
   }
-  static __device__ __forceinline__ float lo(uint32_t w) {
+  // acc + a.lo * b.lo + a.hi * b.hi in fp32 (v_dot2c_f32_f16)
+  static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
     typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-    return (float)__builtin_bit_cast(h2, w)[0];
-  }
-  static __device__ __forceinline__ float hi(uint32_t w) {
-    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-    return (float)__builtin_bit_cast(h2, w)[1];
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, a), __builtin_bit_cast(h2, b), acc, false);
   }
 };
 
@@ -74,11 +71,9 @@ struct Op<__bf16> {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, w), b2{(__bf16)1.f, (__bf16)1.f},
                                            acc, false);
   }
-  static __device__ __forceinline__ float lo(uint32_t w) {
-    return __builtin_bit_cast(float, w << 16);
-  }
-  static __device__ __forceinline__ float hi(uint32_t w) {
-    return __builtin_bit_cast(float, w & 0xffff0000u);
+  static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, a), __builtin_bit_cast(b2, b), acc, false);
   }
 };
 
