@@ -49,8 +49,9 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
-              "(see DESIGN.md, 'More than one GPU')" % args.gpus, file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (sequences and heads are independent, so more "
+              "GPUs would each run their own batch); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
         sys.exit(2)
 
     import torch
