@@ -73,9 +73,9 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
   for (int kb = 0; kb < 2; kb++)
 #pragma unroll
     for (int r = 0; r < 16; r++) {
-      float x = s[kb][r];
-      if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) x = -INFINITY;
-      mxs[kb] = fmaxf(mxs[kb], x);
+      // no mask needed here: the rows of a ragged block past the last key repeat
+      // that key (the fetch clamps the row index), so they cannot raise the maximum
+      mxs[kb] = fmaxf(mxs[kb], s[kb][r]);
     }
   float mx = fmaxf(mxs[0], mxs[1]);
   mx = fmaxf(mx, other_half(mx));
