@@ -95,6 +95,7 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
   float psum = 0.f;
 #pragma unroll
   for (int kb = 0; kb < 2; kb++) {
+    if (RAGGED && kb == 1 && key_base + 32 >= nk) break;  // no key in the second half
     u32x4 va[2][2];  // V^T operands of this half: [16-key step][channel block]
 #pragma unroll
     for (int t2 = 0; t2 < 2; t2++)
