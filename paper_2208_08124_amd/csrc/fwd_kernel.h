@@ -54,29 +54,38 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   // S^T = K Q^T : rows = keys (two blocks of 32), column = query ln
   f32x16 s[2];
+  const bool one_half = RAGGED && key_base + 32 >= nk;  // uniform: no key in the second 32
   {
     u32x4 ka[4][2];
 #pragma unroll
     for (int t = 0; t < 4; t++)
 #pragma unroll
-      for (int kb = 0; kb < 2; kb++) ka[t][kb] = rr.read(sK, kb, t);
+      for (int kb = 0; kb < 2; kb++)
+        if (kb == 0 || !one_half) ka[t][kb] = rr.read(sK, kb, t);
     __builtin_amdgcn_sched_barrier(0);
+    if (one_half) {
 #pragma unroll
-    for (int t = 0; t < 4; t++)
+      for (int t = 0; t < 4; t++) s[0] = Op<T>::mfma(ka[t][0], qb[t], t == 0 ? zero : s[0]);
+    } else {
 #pragma unroll
-      for (int kb = 0; kb < 2; kb++) s[kb] = Op<T>::mfma(ka[t][kb], qb[t], t == 0 ? zero : s[kb]);
+      for (int t = 0; t < 4; t++)
+#pragma unroll
+        for (int kb = 0; kb < 2; kb++) s[kb] = Op<T>::mfma(ka[t][kb], qb[t], t == 0 ? zero : s[kb]);
+    }
   }
   __builtin_amdgcn_sched_barrier(0);
   const int key0 = key_base + 4 * g;      // key of s[0][0]
   float mxs[2] = {-INFINITY, -INFINITY};  // two independent chains
 #pragma unroll
-  for (int kb = 0; kb < 2; kb++)
+  for (int kb = 0; kb < 2; kb++) {
+    if (kb == 1 && one_half) break;
 #pragma unroll
     for (int r = 0; r < 16; r++) {
       // no mask needed here: the rows of a ragged block past the last key repeat
       // that key (the fetch clamps the row index), so they cannot raise the maximum
       mxs[kb] = fmaxf(mxs[kb], s[kb][r]);
     }
+  }
   float mx = fmaxf(mxs[0], mxs[1]);
   mx = fmaxf(mx, other_half(mx));
   const float m_blk = mx * c2;  // c2 >= 0: the sign of the scale was folded into Q
@@ -95,7 +104,7 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
   float psum = 0.f;
 #pragma unroll
   for (int kb = 0; kb < 2; kb++) {
-    if (RAGGED && kb == 1 && key_base + 32 >= nk) break;  // no key in the second half
+    if (kb == 1 && one_half) break;
     u32x4 va[2][2];  // V^T operands of this half: [16-key step][channel block]
 #pragma unroll
     for (int t2 = 0; t2 < 2; t2++)
