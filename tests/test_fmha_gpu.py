@@ -162,6 +162,44 @@ def test_strided_outputs_leave_the_gaps_untouched():
         assert bool((x[:, 1] == 7.0).all())
 
 
+def test_element_offsets_beyond_two_to_the_31():
+    # token stride 32768 elements: tokens from 65536 on start more than 2^31 elements into
+    # their buffer (only the strided rows are ever touched, the buffers are not initialised)
+    lengths = [512] * 128 + [300, 77, 512, 1]
+    b = wl.make_batch(lengths, 16, "f16", seed=51)
+    ref = DeviceBatch(b, True)
+    ref.fwd()
+    ref.bwd(reuse_schedule=True)
+    d = DeviceBatch(b, True)
+    t = b["total_tokens"]
+    assert t > 65536 + 512
+    stride = 32768
+    def wide(src=None):
+        buf = torch.empty((t, stride), dtype=ref.q.dtype, device="cuda")
+        view = buf[:, :16 * 64].view(t, 16, 64)
+        if src is not None:
+            view.copy_(src)
+        return view
+    d.q, d.k, d.v, d.do = wide(ref.q), wide(ref.k), wide(ref.v), wide(ref.do)
+    d.o, d.dq, d.dk, d.dv = wide(), wide(), wide(), wide()
+    d.fwd()
+    d.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    for got, want in ((d.o, ref.o), (d.lse, ref.lse), (d.dq, ref.dq), (d.dk, ref.dk), (d.dv, ref.dv)):
+        assert torch.equal(got, want)
+    # and the last sequences (the ones past 2^31) against the oracle
+    tail = wl.make_batch(lengths[-4:], 16, "f16", seed=51)
+    r0 = int(b["cu_seqlens"][-5])
+    for n in ("q", "k", "v", "do"):
+        tail[n] = b[n][r0:]
+    x = oracle_inputs(tail)
+    o_ref, _ = oracle.fwd(x["q"], x["k"], x["v"], tail["cu_seqlens"], tail["scale"])
+    assert np.abs(to_f64(d.o[r0:]) - o_ref).max() <= O_TOL
+    g_ref = oracle.bwd(x["q"], x["k"], x["v"], x["do"], tail["cu_seqlens"], tail["scale"])
+    for got, want in zip((d.dq, d.dk, d.dv), g_ref):
+        assert np.abs(to_f64(got[r0:]) - want).max() / max(np.abs(want).max(), G_FLOOR) <= G_TOL
+
+
 def test_seqused_zero_negative_and_partial():
     # keys attended per sequence: none, a negative count (treated as none), some, all
     b = wl.make_batch([70, 40, 150, 33], 2, "f16", seed=41)
