@@ -5,7 +5,10 @@
 // One workgroup (4 wavefronts) takes one tile of 128 query rows of one
 // (sequence, head); wavefront w owns rows 32w..32w+31.  Keys and values move
 // 64 rows at a time from HBM straight into a ring of three LDS stages, two
-// blocks ahead of the one being computed, with one barrier per block.
+// blocks ahead of the one being computed, with one barrier per block.  A
+// wavefront's 32 query rows arrive the same way, into rows of the ring that
+// only its own transfers write, together with the first key blocks; its 32
+// output rows leave through the same rows as whole 128-byte rows.
 //
 // The scores are produced TRANSPOSED, S^T = K Q^T, so that in the MFMA result
 // layout every lane holds 16 keys of ONE query: the row maximum and row sum
