@@ -162,6 +162,25 @@ def test_strided_outputs_leave_the_gaps_untouched():
         assert bool((x[:, 1] == 7.0).all())
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_random_small_batches(case):
+    # seeded sweep over lengths (block and tile boundaries +-1 included), head counts,
+    # both dtypes, scales and, in every third case, a random number of attended keys
+    rng = np.random.default_rng(1000 + case)
+    edges = np.array([1, 31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 191, 192, 193, 255, 256, 257, 383, 385, 640])
+    n = int(rng.integers(1, 7))
+    lengths = [int(rng.choice(edges)) if rng.random() < 0.6 else int(rng.integers(1, 400)) for _ in range(n)]
+    if case % 5 == 0:
+        lengths.insert(int(rng.integers(0, n + 1)), 0)
+    heads = int(rng.integers(1, 5))
+    dtype = "f16" if case % 2 == 0 else "bf16"
+    b = wl.make_batch(lengths, heads, dtype, seed=2000 + case)
+    b["scale"] = float(rng.choice([0.125, 0.125, 0.3, -0.125, 1.0 / 64]))
+    if case % 3 == 2:
+        b["seqused"] = np.array([int(rng.integers(0, l + 1)) for l in lengths], dtype=np.int32)
+    run(b, True)
+
+
 def test_element_offsets_beyond_two_to_the_31():
     # token stride 32768 elements: tokens from 65536 on start more than 2^31 elements into
     # their buffer (only the strided rows are ever touched, the buffers are not initialised)
