@@ -251,6 +251,27 @@ def test_stream_order_without_host_sync():
     assert total.item() == ref.o.float().sum().item()
 
 
+def test_two_streams_with_their_own_workspaces():
+    """Independent batches on two streams at once: the only shared state is the library."""
+    ba = wl.make_batch([200, 512, 64], 4, "f16", seed=61)
+    bb = wl.make_batch([17, 300, 129, 96], 4, "bf16", seed=62)
+    ra, rb = run(ba, True), run(bb, True)
+    da, dbb = DeviceBatch(ba, True), DeviceBatch(bb, True)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        with torch.cuda.stream(sa):
+            da.fwd()
+            da.bwd(reuse_schedule=True)
+        with torch.cuda.stream(sb):
+            dbb.fwd()
+            dbb.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    for d, r in ((da, ra), (dbb, rb)):
+        for x, y in ((d.o, r.o), (d.lse, r.lse), (d.dq, r.dq), (d.dk, r.dk), (d.dv, r.dv)):
+            assert torch.equal(x, y)
+
+
 def test_error_codes_need_no_device_work():
     b = wl.make_batch([8, 8], 2, "f16", seed=1, backward=False)
     db = DeviceBatch(b, False)
