@@ -32,6 +32,10 @@
  *   - Arithmetic: 16-bit operands, fp32 accumulation and fp32 softmax state;
  *     the probabilities are rounded to the operand type before they are
  *     multiplied with V (and dO), as is dS before it meets K and Q.
+ *   - The workspace carries state from the forward to the backward call and
+ *     between the two backward passes: calls that may overlap in time (other
+ *     streams, other threads) need workspaces of their own.  The library keeps
+ *     no other state, so such calls are safe.
  *   - Errors are return codes; fmha_last_error() gives a message for the last
  *     failing call on the calling thread.  Validation reads only host memory.
  */
