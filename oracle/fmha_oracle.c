@@ -32,6 +32,17 @@
  * A row with no admissible key (nk_i = 0, only possible through seqused) has
  * O = 0, LSE = -inf and contributes no gradient.
  *
+ * Dropout on the attention probabilities (BERT's training configuration,
+ * Section V-A; the paper does not describe it inside the attention kernel):
+ * the *_dropout entry points take an explicit keep mask M (1 = kept; how it is
+ * drawn is dropout_mask.py's business) and a factor c = 1 / (1 - p):
+ *                         O  = (P o M c) V
+ *                         dV = (P o M c)^T dO
+ *                         dP = (dO V^T) o M c
+ *             D, dS, dQ, dK as above (the softmax itself, and LSE, are unchanged).
+ * Mask layout: sequence i, head h, query r, key j at
+ * keep[keep_off[i] + (h * L_i + r) * L_i + j].
+ *
  * Everything is plain loops in double precision, natural exp/log, parallel
  * over (sequence, head) only.  Build without -ffast-math.
  *
@@ -74,9 +85,9 @@ static double softmax_row(const double *q, const double *kbase, int64_t kstride,
   return m + log(z);
 }
 
-int oracle_fmha_varlen_fwd(const double *q, const double *k, const double *v, const int32_t *cu,
-                           const int32_t *seqused, int B, int H, int D, double scale, double *o,
-                           double *lse) {
+static int fwd_impl(const double *q, const double *k, const double *v, const int32_t *cu,
+                    const int32_t *seqused, int B, int H, int D, double scale, const uint8_t *keep,
+                    const int64_t *keep_off, double keep_scale, double *o, double *lse) {
   if (check_cu(cu, B) || H <= 0 || D <= 0) return 1;
   const int64_t T = cu[B];
   const int64_t ts = (int64_t)H * D; /* token stride */
@@ -104,7 +115,9 @@ int oracle_fmha_varlen_fwd(const double *q, const double *k, const double *v, co
         for (int c = 0; c < D; c++) orow[c] = 0.0;
         for (int j = 0; j < nk; j++) {
           const double *vj = v + (r0 + j) * ts + (int64_t)h * D;
-          for (int c = 0; c < D; c++) orow[c] += p[j] * vj[c];
+          double pj = p[j];
+          if (keep) pj *= keep[keep_off[i] + ((int64_t)h * L + r) * L + j] ? keep_scale : 0.0;
+          for (int c = 0; c < D; c++) orow[c] += pj * vj[c];
         }
         if (lse) lse[(int64_t)h * T + r0 + r] = l;
       }
@@ -114,9 +127,24 @@ int oracle_fmha_varlen_fwd(const double *q, const double *k, const double *v, co
   return fail;
 }
 
-int oracle_fmha_varlen_bwd(const double *q, const double *k, const double *v, const double *dO,
-                           const int32_t *cu, const int32_t *seqused, int B, int H, int D,
-                           double scale, double *dq, double *dk, double *dv) {
+int oracle_fmha_varlen_fwd(const double *q, const double *k, const double *v, const int32_t *cu,
+                           const int32_t *seqused, int B, int H, int D, double scale, double *o,
+                           double *lse) {
+  return fwd_impl(q, k, v, cu, seqused, B, H, D, scale, NULL, NULL, 1.0, o, lse);
+}
+
+int oracle_fmha_varlen_fwd_dropout(const double *q, const double *k, const double *v,
+                                   const int32_t *cu, const int32_t *seqused, int B, int H, int D,
+                                   double scale, const uint8_t *keep, const int64_t *keep_off,
+                                   double keep_scale, double *o, double *lse) {
+  if (!keep || !keep_off) return 1;
+  return fwd_impl(q, k, v, cu, seqused, B, H, D, scale, keep, keep_off, keep_scale, o, lse);
+}
+
+static int bwd_impl(const double *q, const double *k, const double *v, const double *dO,
+                    const int32_t *cu, const int32_t *seqused, int B, int H, int D, double scale,
+                    const uint8_t *keep, const int64_t *keep_off, double keep_scale, double *dq,
+                    double *dk, double *dv) {
   if (check_cu(cu, B) || H <= 0 || D <= 0) return 1;
   const int64_t ts = (int64_t)H * D;
   int fail = 0;
@@ -149,12 +177,15 @@ int oracle_fmha_varlen_bwd(const double *q, const double *k, const double *v, co
           const double *vj = v + (r0 + j) * ts + hb;
           double *dvj = dv + (r0 + j) * ts + hb;
           double t = 0.0;
+          /* M c of this element; 1 without dropout */
+          const double mc =
+              keep ? (keep[keep_off[i] + ((int64_t)h * L + r) * L + j] ? keep_scale : 0.0) : 1.0;
           for (int c = 0; c < D; c++) {
-            dvj[c] += p[j] * gr[c]; /* dV = P^T dO */
-            t += gr[c] * vj[c];     /* dP = dO V^T */
+            dvj[c] += p[j] * mc * gr[c]; /* dV = (P o M c)^T dO */
+            t += gr[c] * vj[c];          /* dO V^T */
           }
-          dp[j] = t;
-          Dr += p[j] * t;
+          dp[j] = t * mc; /* dP = (dO V^T) o M c */
+          Dr += p[j] * dp[j];
         }
         double *dqr = dq + (r0 + r) * ts + hb;
         for (int j = 0; j < nk; j++) {
@@ -171,6 +202,21 @@ int oracle_fmha_varlen_bwd(const double *q, const double *k, const double *v, co
     }
   }
   return fail;
+}
+
+int oracle_fmha_varlen_bwd(const double *q, const double *k, const double *v, const double *dO,
+                           const int32_t *cu, const int32_t *seqused, int B, int H, int D,
+                           double scale, double *dq, double *dk, double *dv) {
+  return bwd_impl(q, k, v, dO, cu, seqused, B, H, D, scale, NULL, NULL, 1.0, dq, dk, dv);
+}
+
+int oracle_fmha_varlen_bwd_dropout(const double *q, const double *k, const double *v,
+                                   const double *dO, const int32_t *cu, const int32_t *seqused,
+                                   int B, int H, int D, double scale, const uint8_t *keep,
+                                   const int64_t *keep_off, double keep_scale, double *dq,
+                                   double *dk, double *dv) {
+  if (!keep || !keep_off) return 1;
+  return bwd_impl(q, k, v, dO, cu, seqused, B, H, D, scale, keep, keep_off, keep_scale, dq, dk, dv);
 }
 
 int oracle_num_threads(void) {

@@ -40,6 +40,16 @@ def _load():
         lib.oracle_fmha_varlen_bwd.argtypes = [dp, dp, dp, dp, ip, ip, ctypes.c_int, ctypes.c_int,
                                                ctypes.c_int, ctypes.c_double, dp, dp, dp]
         lib.oracle_fmha_varlen_bwd.restype = ctypes.c_int
+        bp = ctypes.POINTER(ctypes.c_uint8)
+        lp = ctypes.POINTER(ctypes.c_int64)
+        lib.oracle_fmha_varlen_fwd_dropout.argtypes = [dp, dp, dp, ip, ip, ctypes.c_int, ctypes.c_int,
+                                                       ctypes.c_int, ctypes.c_double, bp, lp,
+                                                       ctypes.c_double, dp, dp]
+        lib.oracle_fmha_varlen_fwd_dropout.restype = ctypes.c_int
+        lib.oracle_fmha_varlen_bwd_dropout.argtypes = [dp, dp, dp, dp, ip, ip, ctypes.c_int,
+                                                       ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                                       bp, lp, ctypes.c_double, dp, dp, dp]
+        lib.oracle_fmha_varlen_bwd_dropout.restype = ctypes.c_int
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -93,4 +103,63 @@ def bwd(q, k, v, d_o, cu_seqlens, scale, seqused=None):
                                         len(cu) - 1, h, d, float(scale), _d(dq), _d(dk), _d(dv))
     if rc:
         raise ValueError("oracle_fmha_varlen_bwd: bad arguments")
+    return dq, dk, dv
+
+
+def _flatten_masks(masks, cu, heads):
+    """Per-sequence [H, L, L] keep masks -> one byte array + the offset of each sequence."""
+    off = np.zeros(len(masks) + 1, dtype=np.int64)
+    for i, m in enumerate(masks):
+        n = int(cu[i + 1] - cu[i])
+        assert m.shape == (heads, n, n), "mask of sequence %d must be [heads, L, L]" % i
+        off[i + 1] = off[i] + m.size
+    flat = np.zeros(max(int(off[-1]), 1), dtype=np.uint8)
+    for i, m in enumerate(masks):
+        flat[off[i]:off[i + 1]] = np.ascontiguousarray(m, dtype=np.uint8).ravel()
+    return flat, off
+
+
+def _b(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+def _l(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+
+
+def fwd_dropout(q, k, v, cu_seqlens, scale, masks, keep_scale, seqused=None):
+    """Forward with an explicit keep mask per sequence ([H, L, L], 1 = kept) on the
+    probabilities and the factor keep_scale = 1 / (1 - p).  Returns (O, LSE)."""
+    q, k, v = _prep(q), _prep(k), _prep(v)
+    assert q.shape == k.shape == v.shape
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    su = None if seqused is None else np.ascontiguousarray(seqused, dtype=np.int32)
+    t, h, d = q.shape
+    assert cu[-1] == t and len(masks) == len(cu) - 1
+    flat, off = _flatten_masks(masks, cu, h)
+    o = np.zeros_like(q)
+    lse = np.zeros((h, t), dtype=np.float64)
+    rc = _load().oracle_fmha_varlen_fwd_dropout(_d(q), _d(k), _d(v), _i(cu), _i(su), len(cu) - 1,
+                                                h, d, float(scale), _b(flat), _l(off),
+                                                float(keep_scale), _d(o), _d(lse))
+    if rc:
+        raise ValueError("oracle_fmha_varlen_fwd_dropout: bad arguments")
+    return o, lse
+
+
+def bwd_dropout(q, k, v, d_o, cu_seqlens, scale, masks, keep_scale, seqused=None):
+    """Backward of fwd_dropout for the same masks.  Returns (dQ, dK, dV)."""
+    q, k, v, d_o = _prep(q), _prep(k), _prep(v), _prep(d_o)
+    assert q.shape == k.shape == v.shape == d_o.shape
+    cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+    su = None if seqused is None else np.ascontiguousarray(seqused, dtype=np.int32)
+    t, h, d = q.shape
+    assert cu[-1] == t and len(masks) == len(cu) - 1
+    flat, off = _flatten_masks(masks, cu, h)
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(q), np.zeros_like(q)
+    rc = _load().oracle_fmha_varlen_bwd_dropout(_d(q), _d(k), _d(v), _d(d_o), _i(cu), _i(su),
+                                                len(cu) - 1, h, d, float(scale), _b(flat), _l(off),
+                                                float(keep_scale), _d(dq), _d(dk), _d(dv))
+    if rc:
+        raise ValueError("oracle_fmha_varlen_bwd_dropout: bad arguments")
     return dq, dk, dv
