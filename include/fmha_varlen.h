@@ -122,6 +122,52 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
                     const void* o, const void* d_o, const float* lse, void* dq, void* dk,
                     void* dv, void* stream);
 
+/* ---- Dropout on the attention probabilities -------------------------------
+ * BERT trains with dropout on the attention probabilities (the model of the
+ * paper's Section V-A); the paper does not describe how its attention kernel
+ * draws it.  Here the mask is a pure function of (seed, sequence start, head,
+ * query, key), so the backward call regenerates the mask the forward call used
+ * and nothing is stored:
+ *   - the 4 x 4 block (Q4, K4) = (q >> 2, k >> 2) of the score matrix of the
+ *     sequence that starts at packed row r0, head h (q, k counted from the start
+ *     of the sequence) owns one call of the counter-based generator Philox4x32
+ *     with 10 rounds (Salmon, Moraes, Dror, Shaw, SC 2011), counter words
+ *     (K4, Q4, r0, h), key words (seed & 0xffffffff, seed >> 32);
+ *   - with B[x][y] = byte y (little endian) of output word x, element (q, k)
+ *     reads x = ((q & 3) - (k >> 3)) & 3 and y = ((k & 3) - (q >> 3)) & 3;
+ *   - the element is kept iff that byte >= t, t = round(256 p) clamped to
+ *     [0, 255]: the probability applied is t / 256, and what is kept is
+ *     multiplied by 256 / (256 - t).
+ * Forward:  O = (P o M) V with M the scaled mask; LSE is that of the undropped
+ * softmax.  Backward: dV = (P o M)^T dO, dP = (dO V^T) o M, the rest as without
+ * dropout.  A caller wanting a fresh mask per layer and step passes a fresh seed. */
+typedef struct fmha_dropout {
+  float p;       /* drop probability, 0 <= p < 1; applied as round(256 p) / 256 */
+  uint64_t seed; /* generator key */
+} fmha_dropout_t;
+
+/* fmha_varlen_fwd / fmha_varlen_bwd with dropout; `dropout` is host memory, read
+ * during the call.  All other arguments, conventions and error codes as above;
+ * p outside [0, 1) or a null `dropout` -> FMHA_ERR_INVALID_ARG.  The backward call
+ * must be given the p and seed of the forward call that produced o and lse. */
+int fmha_varlen_fwd_dropout(const fmha_varlen_params_t* p, const fmha_dropout_t* dropout,
+                            const void* q, const void* k, const void* v, void* o, float* lse,
+                            void* stream);
+int fmha_varlen_bwd_dropout(const fmha_varlen_params_t* p, const fmha_dropout_t* dropout,
+                            const void* q, const void* k, const void* v, const void* o,
+                            const void* d_o, const float* lse, void* dq, void* dk, void* dv,
+                            void* stream);
+
+/* Writes the keep mask itself, for tests and debugging: mask is device memory,
+ * heads * total_tokens rows of row_bytes bytes (row_bytes >= the longest sequence,
+ * and >= max_seqlen if that is given); byte k of row h * total_tokens + t becomes 1 if
+ * key k of token t's sequence is kept for query t under head h, else 0, for k < L of
+ * that sequence; other bytes are left alone.  orientation 0 / 1 selects the code path
+ * of the forward and dQ kernels / of the dK/dV kernel; both write the same mask.
+ * Uses the workspace for the tile list like the other calls. */
+int fmha_dropout_keep_mask(const fmha_varlen_params_t* p, const fmha_dropout_t* dropout,
+                           int32_t orientation, int32_t row_bytes, uint8_t* mask, void* stream);
+
 /* Number of 128-row tiles the schedule holds at most for this shape (host
  * arithmetic), and a device-to-host-free way for tests to locate the tile list
  * inside the workspace: the list starts at byte offset *list_offset and holds

@@ -8,6 +8,10 @@
 //       queries  S = Q K^T,  dP = dO V^T,  P, dS as above,
 //       dV^T += dO^T P,  dK^T += Q^T dS.
 //
+// With dropout (DROP) the mask M is regenerated from the seed (dropout.h):
+// dP = (dO V^T) o M / (1-p) in both passes and dV^T += dO^T (P o M) with the
+// factor 1/(1-p) applied to the finished rows; D = rowsum(dO o O) as before.
+//
 // Both orientations are chosen so that the MFMA result tile of the first two
 // products has, in every lane, the reduction index of the following product
 // spread over its registers; P and dS then go back in as B operands without
@@ -18,6 +22,7 @@
 // pass 2) moves from HBM straight into a ring of swizzled LDS stages, two
 // blocks ahead of its use, one barrier per block.
 #pragma once
+#include "dropout.h"
 #include "kernel_args.h"
 #include "mfma_tiles.h"
 
@@ -35,11 +40,12 @@ static __device__ __forceinline__ u32x4 pack8(const float (&x)[16], int t2) {
 // ---------------------------------------------------------------- pass 1: dQ
 // One block of 64 keys for one wavefront (32 queries), done as two halves of 32 keys
 // so that only one half's scores and operands are live at a time.
-template <typename T, bool RAGGED>
+template <typename T, bool RAGGED, bool DROP>
 __device__ __forceinline__ void dq_block(f32x16 (&dq)[2], const uint16_t* sK, const uint16_t* sV,
                                          const u32x4 (&qb)[4], const u32x4 (&gb)[4], float c2,
                                          float lse2, float dsum, int key_base, int nk, int g,
-                                         const RowRead& rr, const ColRead& cr) {
+                                         const RowRead& rr, const ColRead& cr, int q4, int ln, int r0,
+                                         int head, const DropArgs& drop) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int kb = 0; kb < 2; kb++) {
@@ -58,6 +64,8 @@ __device__ __forceinline__ void dq_block(f32x16 (&dq)[2], const uint16_t* sK, co
       s = Op<T>::mfma(ka[t], qb[t], t == 0 ? zero : s);
       dp = Op<T>::mfma(va[t], gb[t], t == 0 ? zero : dp);
     }
+    uint32_t kb8[4];  // mask bytes: independent of the products just issued
+    if (DROP) keep_bytes<false>(kb8, q4, ((key_base + 32 * kb) >> 2) + g, ln, r0, head, drop);
     __builtin_amdgcn_sched_barrier(0);
     u32x4 kT[2][2];
 #pragma unroll
@@ -71,7 +79,8 @@ __device__ __forceinline__ void dq_block(f32x16 (&dq)[2], const uint16_t* sK, co
     for (int r = 0; r < 16; r++) {
       float p = fast_exp2(__builtin_fmaf(s[r], c2, -lse2));
       if (RAGGED && key0 + 8 * (r >> 2) + (r & 3) >= nk) p = 0.f;
-      ds[r] = p * (dp[r] - dsum);
+      const float dpr = DROP ? (kept(kb8, r, drop.thr) ? dp[r] * drop.rp : 0.f) : dp[r];
+      ds[r] = p * (dpr - dsum);
     }
     u32x4 dsb[2];
 #pragma unroll
@@ -84,8 +93,9 @@ __device__ __forceinline__ void dq_block(f32x16 (&dq)[2], const uint16_t* sK, co
   }
 }
 
-template <typename T>
-__global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
+template <typename T, bool DROP>
+__global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const BwdArgs a) {
+  constexpr int kPerCu = DROP ? 2 : 3;  // workgroups per compute unit (the launcher's grid assumes it)
   __shared__ __align__(1024) uint16_t ring[kBwdStages][2][kTileElems];  // [stage][K|V]
 
   const int tid = threadIdx.x;
@@ -94,7 +104,7 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
   const int heads = a.pb.heads;
   const int n_items = tile_count(a.pb) * heads;
   const float c2 = a.pb.scale * kLog2e;
-  const int slot = blockIdx.x / max(gridDim.x / 3u, 1u);  // which of the 3 workgroups per compute unit
+  const int slot = blockIdx.x / max(gridDim.x / (unsigned)kPerCu, 1u);  // which of the workgroups of its compute unit
   const DmaLane dl(wave, lane);
   const RowRead rr(ln, g);
   const ColRead cr(lane);
@@ -211,16 +221,17 @@ __global__ __launch_bounds__(kThreads, 3) void bwd_dq_kernel(const BwdArgs a) {
       else
         wait_vmem<0>();
       __syncthreads();  // everyone's pieces; and everyone is done with block kt-1's stage
-      rotate_priority(kt, slot, 3);
+      rotate_priority(kt, slot, kPerCu);
       const int ahead = stage == 0 ? kBwdStages - 1 : stage - 1;  // (kt + 2) % 3
       if (kt + 2 < n) start_block(kt + 2, ahead);
       if (wave_on) {
         const uint16_t* sK = &ring[0][0][0] + stage * (2 * kTileElems);
         const uint16_t* sV = sK + kTileElems;
+        const int q4 = qrow >> 2;
         if ((kt + 1) * kBlockKeys > nk)
-          dq_block<T, true>(dq, sK, sV, qb, gb, c2, lse2, dsum, kt * kBlockKeys, nk, g, rr, cr);
+          dq_block<T, true, DROP>(dq, sK, sV, qb, gb, c2, lse2, dsum, kt * kBlockKeys, nk, g, rr, cr, q4, ln, r0, head, a.drop);
         else
-          dq_block<T, false>(dq, sK, sV, qb, gb, c2, lse2, dsum, kt * kBlockKeys, nk, g, rr, cr);
+          dq_block<T, false, DROP>(dq, sK, sV, qb, gb, c2, lse2, dsum, kt * kBlockKeys, nk, g, rr, cr, q4, ln, r0, head, a.drop);
       }
       stage = stage == kBwdStages - 1 ? 0 : stage + 1;
     }
@@ -258,10 +269,12 @@ struct DkvStage {
 // No masking is needed here: query rows past the end of the sequence carry
 // LSE = +inf in the stage (so P = 0), and the columns of keys that are masked
 // or past the end are independent of all others and are simply not stored.
-template <typename T>
+template <typename T, bool DROP>
 __device__ __forceinline__ void dkv_block(f32x16 (&dk)[2], f32x16 (&dv)[2], const DkvStage* st,
                                           int qb, const u32x4 (&kb4)[4], const u32x4 (&vb4)[4],
-                                          float c2, int g, const RowRead& rr, const ColRead& cr) {
+                                          float c2, int g, const RowRead& rr, const ColRead& cr,
+                                          int k4, int q_base, int ln, int r0, int head,
+                                          const DropArgs& drop) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   u32x4 qa[4], ga[4];
 #pragma unroll
@@ -277,6 +290,8 @@ __device__ __forceinline__ void dkv_block(f32x16 (&dk)[2], f32x16 (&dv)[2], cons
     s = Op<T>::mfma(qa[t], kb4[t], t == 0 ? zero : s);
     dp = Op<T>::mfma(ga[t], vb4[t], t == 0 ? zero : dp);
   }
+  uint32_t kb8[4];  // mask bytes: independent of the products just issued
+  if (DROP) keep_bytes<true>(kb8, k4, ((q_base + 32 * qb) >> 2) + g, ln, r0, head, drop);
   __builtin_amdgcn_sched_barrier(0);
   // rows 32qb + 8j + 4g + {0..3}: their statistics sit side by side
   float4 l4[4], d4[4];
@@ -299,8 +314,14 @@ __device__ __forceinline__ void dkv_block(f32x16 (&dk)[2], f32x16 (&dv)[2], cons
 #pragma unroll
     for (int e = 0; e < 4; e++) {
       const float pe = fast_exp2(__builtin_fmaf(s[4 * j + e], c2, -lv[e]));
-      p[4 * j + e] = pe;
-      ds[4 * j + e] = pe * (dp[4 * j + e] - dvv[e]);
+      if (DROP) {
+        const bool on = kept(kb8, 4 * j + e, drop.thr);
+        p[4 * j + e] = on ? pe : 0.f;
+        ds[4 * j + e] = pe * ((on ? dp[4 * j + e] * drop.rp : 0.f) - dvv[e]);
+      } else {
+        p[4 * j + e] = pe;
+        ds[4 * j + e] = pe * (dp[4 * j + e] - dvv[e]);
+      }
     }
   }
   u32x4 pb[2], dsb[2];
@@ -327,7 +348,7 @@ __device__ __forceinline__ void dkv_block(f32x16 (&dk)[2], f32x16 (&dv)[2], cons
     for (int cb = 0; cb < 2; cb++) dk[cb] = Op<T>::mfma(qT[t2][cb], dsb[t2], dk[cb]);
 }
 
-template <typename T>
+template <typename T, bool DROP>
 __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
   __shared__ __align__(1024) DkvStage ring[kBwdStages];
 
@@ -433,8 +454,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
       if (qt + 2 < n) start_block(qt + 2, ahead);
       if (wave_on) {
         const DkvStage* st = &ring[stage];
-        dkv_block<T>(dk, dv, st, 0, kb4, vb4, c2, g, rr, cr);
-        if (qt * kBlockKeys + 32 < len) dkv_block<T>(dk, dv, st, 1, kb4, vb4, c2, g, rr, cr);
+        const int k4 = krow >> 2;
+        dkv_block<T, DROP>(dk, dv, st, 0, kb4, vb4, c2, g, rr, cr, k4, qt * kBlockKeys, ln, r0, head, a.drop);
+        if (qt * kBlockKeys + 32 < len)
+          dkv_block<T, DROP>(dk, dv, st, 1, kb4, vb4, c2, g, rr, cr, k4, qt * kBlockKeys, ln, r0, head, a.drop);
       }
       stage = stage == kBwdStages - 1 ? 0 : stage + 1;
     }
@@ -454,7 +477,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
       const int n_rows = len - (ti.row0 + 32 * wave);
       store_rows<T>(dk, a.pb.scale, ring[kBwdStages - 1].q, wave, a.dk + tok * a.dk_stride + head * kHeadDim,
                     a.dk_stride, n_rows);
-      store_rows<T>(dv, 1.f, ring[kBwdStages - 2].q, wave, a.dv + tok * a.dv_stride + head * kHeadDim,
+      store_rows<T>(dv, DROP ? a.drop.rp : 1.f, ring[kBwdStages - 2].q, wave, a.dv + tok * a.dv_stride + head * kHeadDim,
                     a.dv_stride, n_rows);
     }
   }

@@ -11,6 +11,7 @@
 #include "../../include/fmha_varlen.h"
 #include "bwd_kernels.h"
 #include "fwd_kernel.h"
+#include "keep_mask_kernel.h"
 #include "schedule.h"
 
 namespace {
@@ -156,6 +157,26 @@ fmha::Problem problem_of(const fmha_varlen_params_t* p, const Workspace& w) {
   return pb;
 }
 
+// Dropout arguments for the kernels; d == nullptr means no dropout.
+int drop_args(const fmha_dropout_t* d, bool required, fmha::DropArgs* out) {
+  *out = fmha::DropArgs{0u, 0u, 0u, 1.f};
+  if (!d) return required ? fail(FMHA_ERR_INVALID_ARG, "dropout is null") : FMHA_OK;
+  if (!(d->p >= 0.f && d->p < 1.f)) return fail(FMHA_ERR_INVALID_ARG, "dropout p=%g is not in [0, 1)", (double)d->p);
+  int t = (int)(256.f * d->p + 0.5f);  // p is exactly representable times 256: no double rounding
+  if (t > 255) t = 255;
+  out->thr = (uint32_t)t;
+  out->k0 = (uint32_t)(d->seed & 0xffffffffu);
+  out->k1 = (uint32_t)(d->seed >> 32);
+  out->rp = 256.f / (float)(256 - t);
+  return FMHA_OK;
+}
+
+int run_fwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dropout, const void* q,
+            const void* k, const void* v, void* o, float* lse, void* stream);
+int run_bwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dropout, const void* q,
+            const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
+            void* dk, void* dv, void* stream);
+
 }  // namespace
 
 extern "C" {
@@ -180,8 +201,62 @@ int32_t fmha_varlen_schedule_info(int32_t batch, int32_t total_tokens, int32_t m
 
 int fmha_varlen_fwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
                     void* o, float* lse, void* stream) {
+  return run_fwd(p, nullptr, false, q, k, v, o, lse, stream);
+}
+
+int fmha_varlen_fwd_dropout(const fmha_varlen_params_t* p, const fmha_dropout_t* dropout, const void* q,
+                            const void* k, const void* v, void* o, float* lse, void* stream) {
+  return run_fwd(p, dropout, true, q, k, v, o, lse, stream);
+}
+
+int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
+                    const void* o, const void* d_o, const float* lse, void* dq, void* dk,
+                    void* dv, void* stream) {
+  return run_bwd(p, nullptr, false, q, k, v, o, d_o, lse, dq, dk, dv, stream);
+}
+
+int fmha_varlen_bwd_dropout(const fmha_varlen_params_t* p, const fmha_dropout_t* dropout, const void* q,
+                            const void* k, const void* v, const void* o, const void* d_o,
+                            const float* lse, void* dq, void* dk, void* dv, void* stream) {
+  return run_bwd(p, dropout, true, q, k, v, o, d_o, lse, dq, dk, dv, stream);
+}
+
+int fmha_dropout_keep_mask(const fmha_varlen_params_t* p, const fmha_dropout_t* dropout, int32_t orientation,
+                           int32_t row_bytes, uint8_t* mask, void* stream) {
   int rc = check_common(p, false);
   if (rc) return rc;
+  fmha::DropArgs da;
+  if ((rc = drop_args(dropout, true, &da))) return rc;
+  if (!mask) return fail(FMHA_ERR_INVALID_ARG, "mask is null");
+  if (orientation != 0 && orientation != 1) return fail(FMHA_ERR_INVALID_ARG, "orientation=%d is neither 0 nor 1", orientation);
+  if (row_bytes <= 0) return fail(FMHA_ERR_INVALID_ARG, "row_bytes=%d must be positive", row_bytes);
+  if (p->max_seqlen > row_bytes) return fail(FMHA_ERR_INVALID_ARG, "row_bytes=%d is smaller than max_seqlen=%d", row_bytes, p->max_seqlen);
+  g_err[0] = 0;
+  if (p->batch == 0 || p->total_tokens == 0) return FMHA_OK;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Workspace w = carve(p->workspace, p->batch, p->total_tokens, p->heads);
+  if ((rc = launch_schedule(p, w, st))) return rc;
+  const fmha::Problem pb = problem_of(p, w);
+  const unsigned grid = grid_for(p, 4);
+  if (orientation == 0)
+    fmha::keep_mask_kernel<false><<<grid, fmha::kThreads, 0, st>>>(pb, da, mask, row_bytes);
+  else
+    fmha::keep_mask_kernel<true><<<grid, fmha::kThreads, 0, st>>>(pb, da, mask, row_bytes);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(FMHA_ERR_HIP, "keep-mask launch failed: %s", hipGetErrorString(e));
+  return FMHA_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+int run_fwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dropout, const void* q,
+            const void* k, const void* v, void* o, float* lse, void* stream) {
+  int rc = check_common(p, false);
+  if (rc) return rc;
+  fmha::DropArgs da;
+  if ((rc = drop_args(d, with_dropout, &da))) return rc;
   if ((rc = check_ptr("q", q)) || (rc = check_ptr("k", k)) || (rc = check_ptr("v", v)) ||
       (rc = check_ptr("o", o)) || (rc = check_ptr("lse", lse)))
     return rc;
@@ -204,20 +279,32 @@ int fmha_varlen_fwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   a.o = static_cast<uint16_t*>(o);
   a.lse = lse;
   const unsigned grid = grid_for(p, 3);
-  if (p->dtype == FMHA_F16)
-    fmha::fmha_fwd_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
-  else
-    fmha::fmha_fwd_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
+  a.drop = da;
+  // p = 0 (threshold 0) keeps everything: the plain kernels serve it
+  if (da.thr == 0) {
+    if (p->dtype == FMHA_F16)
+      fmha::fmha_fwd_kernel<_Float16, false><<<grid, fmha::kThreads, 0, st>>>(a);
+    else
+      fmha::fmha_fwd_kernel<__bf16, false><<<grid, fmha::kThreads, 0, st>>>(a);
+  } else {
+    const unsigned grid2 = grid_for(p, 2);
+    if (p->dtype == FMHA_F16)
+      fmha::fmha_fwd_kernel<_Float16, true><<<grid2, fmha::kThreads, 0, st>>>(a);
+    else
+      fmha::fmha_fwd_kernel<__bf16, true><<<grid2, fmha::kThreads, 0, st>>>(a);
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FMHA_ERR_HIP, "forward launch failed: %s", hipGetErrorString(e));
   return FMHA_OK;
 }
 
-int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
-                    const void* o, const void* d_o, const float* lse, void* dq, void* dk,
-                    void* dv, void* stream) {
+int run_bwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dropout, const void* q,
+            const void* k, const void* v, const void* o, const void* d_o, const float* lse, void* dq,
+            void* dk, void* dv, void* stream) {
   int rc = check_common(p, true);
   if (rc) return rc;
+  fmha::DropArgs da;
+  if ((rc = drop_args(d, with_dropout, &da))) return rc;
   if ((p->flags & FMHA_FLAG_BWD_ONLY_DQ) && (p->flags & FMHA_FLAG_BWD_ONLY_DKV))
     return fail(FMHA_ERR_INVALID_ARG, "FMHA_FLAG_BWD_ONLY_DQ and FMHA_FLAG_BWD_ONLY_DKV exclude each other");
   if ((rc = check_ptr("q", q)) || (rc = check_ptr("k", k)) || (rc = check_ptr("v", v)) ||
@@ -241,6 +328,7 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   Workspace w = carve(p->workspace, p->batch, p->total_tokens, p->heads);
   if ((rc = launch_schedule(p, w, st))) return rc;
   a.pb = problem_of(p, w);
+  a.drop = da;
   a.q = static_cast<const uint16_t*>(q);
   a.k = static_cast<const uint16_t*>(k);
   a.v = static_cast<const uint16_t*>(v);
@@ -255,16 +343,26 @@ int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k,
   const unsigned grid_dq = grid_for(p, 3), grid = grid_for(p, 2);
   const bool run_dq = !(p->flags & FMHA_FLAG_BWD_ONLY_DKV);
   const bool run_dkv = !(p->flags & FMHA_FLAG_BWD_ONLY_DQ);
-  if (p->dtype == FMHA_F16) {
-    if (run_dq) fmha::bwd_dq_kernel<_Float16><<<grid_dq, fmha::kThreads, 0, st>>>(a);
-    if (run_dkv) fmha::bwd_dkv_kernel<_Float16><<<grid, fmha::kThreads, 0, st>>>(a);
+  if (da.thr == 0) {
+    if (p->dtype == FMHA_F16) {
+      if (run_dq) fmha::bwd_dq_kernel<_Float16, false><<<grid_dq, fmha::kThreads, 0, st>>>(a);
+      if (run_dkv) fmha::bwd_dkv_kernel<_Float16, false><<<grid, fmha::kThreads, 0, st>>>(a);
+    } else {
+      if (run_dq) fmha::bwd_dq_kernel<__bf16, false><<<grid_dq, fmha::kThreads, 0, st>>>(a);
+      if (run_dkv) fmha::bwd_dkv_kernel<__bf16, false><<<grid, fmha::kThreads, 0, st>>>(a);
+    }
   } else {
-    if (run_dq) fmha::bwd_dq_kernel<__bf16><<<grid_dq, fmha::kThreads, 0, st>>>(a);
-    if (run_dkv) fmha::bwd_dkv_kernel<__bf16><<<grid, fmha::kThreads, 0, st>>>(a);
+    if (p->dtype == FMHA_F16) {
+      if (run_dq) fmha::bwd_dq_kernel<_Float16, true><<<grid, fmha::kThreads, 0, st>>>(a);
+      if (run_dkv) fmha::bwd_dkv_kernel<_Float16, true><<<grid, fmha::kThreads, 0, st>>>(a);
+    } else {
+      if (run_dq) fmha::bwd_dq_kernel<__bf16, true><<<grid, fmha::kThreads, 0, st>>>(a);
+      if (run_dkv) fmha::bwd_dkv_kernel<__bf16, true><<<grid, fmha::kThreads, 0, st>>>(a);
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FMHA_ERR_HIP, "backward launch failed: %s", hipGetErrorString(e));
   return FMHA_OK;
 }
 
-}  // extern "C"
+}  // namespace

@@ -30,6 +30,7 @@
 // rescaled.  The result is the same softmax: the maximum cancels between
 // numerator and row sum.
 #pragma once
+#include "dropout.h"
 #include "kernel_args.h"
 #include "mfma_tiles.h"
 
@@ -50,10 +51,14 @@ struct FwdAcc {
 // compiler from sinking each read next to its use, which would serialise LDS
 // latency with every MFMA); the transpose reads of V fly during the
 // exponentials.
-template <typename T, bool RAGGED>
+// DROP: dropout on the probabilities.  q4 = (this lane's query) >> 2; the running row sum
+// then takes the probabilities before the mask, the second product those that are kept
+// (their common factor 1/(1-p) is applied once, to the finished rows).
+template <typename T, bool RAGGED, bool DROP>
 __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const uint16_t* sV,
                                           const u32x4 (&qb)[4], float c2, int key_base, int nk,
-                                          int g, const RowRead& rr, const ColRead& cr) {
+                                          int g, const RowRead& rr, const ColRead& cr, int q4,
+                                          int ln, int r0, int head, const DropArgs& drop) {
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   // S^T = K Q^T : rows = keys (two blocks of 32), column = query ln
   f32x16 s[2];
@@ -75,6 +80,13 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
 #pragma unroll
         for (int kb = 0; kb < 2; kb++) s[kb] = Op<T>::mfma(ka[t][kb], qb[t], t == 0 ? zero : s[kb]);
     }
+  }
+  // the mask bytes do not depend on the scores: their arithmetic fills the time the
+  // matrix cores need for the products just issued
+  uint32_t kb8[2][4];
+  if (DROP) {
+    keep_bytes<false>(kb8[0], q4, (key_base >> 2) + g, ln, r0, head, drop);
+    if (!one_half) keep_bytes<false>(kb8[1], q4, ((key_base + 32) >> 2) + g, ln, r0, head, drop);
   }
   __builtin_amdgcn_sched_barrier(0);
   const int key0 = key_base + 4 * g;      // key of s[0][0]
@@ -118,6 +130,10 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
     for (int r = 0; r < 16; r++) {
       p[r] = fast_exp2(__builtin_fmaf(s[kb][r], c2, neg_m));
       if (RAGGED && key0 + 32 * kb + 8 * (r >> 2) + (r & 3) >= nk) p[r] = 0.f;
+      if (DROP) {
+        psum += p[r];
+        if (!kept(kb8[kb], r, drop.thr)) p[r] = 0.f;
+      }
     }
     u32x4 pb[2];  // P^T as B operands, one per 16-key step
 #pragma unroll
@@ -126,7 +142,7 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
 #pragma unroll
       for (int e = 0; e < 4; e++) {
         w[e] = Op<T>::pack2(p[8 * t2 + 2 * e], p[8 * t2 + 2 * e + 1]);
-        psum = Op<T>::add_pair(w[e], psum);  // sums what actually multiplies V
+        if (!DROP) psum = Op<T>::add_pair(w[e], psum);  // sums what actually multiplies V
       }
       pb[t2] = w;
     }
@@ -139,8 +155,9 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
   acc.l_run += psum;
 }
 
-template <typename T>
-__global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) {
+template <typename T, bool DROP>
+__global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void fmha_fwd_kernel(const FwdArgs a) {
+  constexpr int kPerCu = DROP ? 2 : 3;  // workgroups per compute unit (the launcher's grid assumes it)
   __shared__ __align__(1024) uint16_t ring[kFwdStages][2][kTileElems];  // [stage][K|V]
 
   const int tid = threadIdx.x;
@@ -150,7 +167,7 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
   const int n_items = tile_count(a.pb) * heads;
   const float c2 = fabsf(a.pb.scale) * kLog2e;  // scores are kept in the log2 domain
   const uint32_t qflip = a.pb.scale < 0.f ? 0x80008000u : 0u;
-  const int slot = blockIdx.x / max(gridDim.x / 3u, 1u);  // which of the 3 workgroups per compute unit
+  const int slot = blockIdx.x / max(gridDim.x / (unsigned)kPerCu, 1u);  // which of the workgroups of its compute unit
   const DmaLane dl(wave, lane);
   const RowRead rr(ln, g);
   const ColRead cr(lane);
@@ -252,16 +269,17 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
       else
         wait_vmem<0>();
       __syncthreads();  // everyone's pieces landed; everyone is done with block kt-1's stage
-      rotate_priority(kt, slot, 3);
+      rotate_priority(kt, slot, kPerCu);
       const int ahead = stage == 0 ? kFwdStages - 1 : stage - 1;  // (kt + 2) % 3
       if (kt + 2 < n) start_block(kt + 2, ahead);
       if (wave_on) {
         const uint16_t* sK = &ring[0][0][0] + stage * (2 * kTileElems);
         const uint16_t* sV = sK + kTileElems;
+        const int q4 = (ti.row0 + 32 * wave + ln) >> 2;
         if ((kt + 1) * kBlockKeys > nk)
-          fwd_block<T, true>(acc, sK, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
+          fwd_block<T, true, DROP>(acc, sK, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr, q4, ln, r0, head, a.drop);
         else
-          fwd_block<T, false>(acc, sK, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr);
+          fwd_block<T, false, DROP>(acc, sK, sV, qb, c2, kt * kBlockKeys, nk, g, rr, cr, q4, ln, r0, head, a.drop);
       }
       stage = stage == kFwdStages - 1 ? 0 : stage + 1;
     }
@@ -271,7 +289,7 @@ __global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) 
     // whole rows, turned around in the wavefront's private rows of the last stage)
     if (wave_on) {
       const float l_tot = acc.l_run + other_half(acc.l_run);
-      const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+      const float inv = l_tot > 0.f ? (DROP ? a.drop.rp : 1.f) / l_tot : 0.f;
       const int le = lane_id();
       const int qrow = ti.row0 + 32 * wave + (le & 31);  // this lane's query, within the sequence
       if (qrow < len && le < 32)

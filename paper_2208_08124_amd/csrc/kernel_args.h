@@ -27,8 +27,16 @@ struct Problem {
   float scale;
 };
 
+// Dropout on the attention probabilities (see dropout.h).
+struct DropArgs {
+  uint32_t thr;     // an element is dropped iff its random byte is < thr; 0 = dropout off
+  uint32_t k0, k1;  // generator key = the two halves of the seed
+  float rp;         // 256 / (256 - thr), multiplies what is kept
+};
+
 struct FwdArgs {
   Problem pb;
+  DropArgs drop;
   const uint16_t *q, *k, *v;
   uint16_t* o;
   float* lse;  // [H, T]
@@ -37,6 +45,7 @@ struct FwdArgs {
 
 struct BwdArgs {
   Problem pb;
+  DropArgs drop;
   const uint16_t *q, *k, *v, *o, *d_o;
   const float* lse;  // [H, T]
   float* dsum;       // [H, T] rowsum(dO o O), workspace (written by the dQ pass)

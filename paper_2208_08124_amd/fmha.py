@@ -22,6 +22,7 @@ FMHA_FLAG_BWD_ONLY_DQ = 2
 FMHA_FLAG_BWD_ONLY_DKV = 4
 
 EXPORTS = ("fmha_varlen_workspace_size", "fmha_varlen_fwd", "fmha_varlen_bwd",
+           "fmha_varlen_fwd_dropout", "fmha_varlen_bwd_dropout", "fmha_dropout_keep_mask",
            "fmha_varlen_schedule_info", "fmha_last_error")
 
 
@@ -39,6 +40,11 @@ class Params(ctypes.Structure):
         ("seqused", ctypes.c_void_p), ("workspace", ctypes.c_void_p),
         ("workspace_bytes", ctypes.c_size_t),
     ]
+
+
+class Dropout(ctypes.Structure):
+    """Mirror of fmha_dropout_t."""
+    _fields_ = [("p", ctypes.c_float), ("seed", ctypes.c_uint64)]
 
 
 class FmhaError(RuntimeError):
@@ -66,6 +72,13 @@ def lib():
         L.fmha_varlen_fwd.restype = ctypes.c_int
         L.fmha_varlen_bwd.argtypes = [ctypes.POINTER(Params)] + [vp] * 10
         L.fmha_varlen_bwd.restype = ctypes.c_int
+        dp = ctypes.POINTER(Dropout)
+        L.fmha_varlen_fwd_dropout.argtypes = [ctypes.POINTER(Params), dp, vp, vp, vp, vp, vp, vp]
+        L.fmha_varlen_fwd_dropout.restype = ctypes.c_int
+        L.fmha_varlen_bwd_dropout.argtypes = [ctypes.POINTER(Params), dp] + [vp] * 10
+        L.fmha_varlen_bwd_dropout.restype = ctypes.c_int
+        L.fmha_dropout_keep_mask.argtypes = [ctypes.POINTER(Params), dp, ctypes.c_int32, ctypes.c_int32, vp, vp]
+        L.fmha_dropout_keep_mask.restype = ctypes.c_int
         L.fmha_varlen_schedule_info.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_size_t)] * 2
         L.fmha_varlen_schedule_info.restype = ctypes.c_int32
         L.fmha_last_error.restype = ctypes.c_char_p
@@ -140,27 +153,67 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+def _dropout(dropout):
+    """(p, seed) -> fmha_dropout_t"""
+    p, seed = dropout
+    return Dropout(float(p), int(seed) & 0xFFFFFFFFFFFFFFFF)
+
+
 def fmha_varlen_fwd(q, k, v, cu_seqlens, max_seqlen, scale, o, lse, workspace, *,
-                    seqused=None, cu_seqlens_host=None, reuse_schedule=False):
-    """Enqueue the forward pass on torch's current stream; fills `o` and `lse` ([H, T] fp32)."""
+                    seqused=None, cu_seqlens_host=None, reuse_schedule=False, dropout=None):
+    """Enqueue the forward pass on torch's current stream; fills `o` and `lse` ([H, T] fp32).
+    `dropout` = (p, seed) selects fmha_varlen_fwd_dropout."""
     p, keep = _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host, reuse_schedule)
     p.q_stride, p.k_stride, p.v_stride, p.o_stride = map(_tok_stride, (q, k, v, o))
     assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.numel() == q.shape[0] * q.shape[1]
-    _check(lib().fmha_varlen_fwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
-                                 o.data_ptr(), lse.data_ptr(), _stream()))
+    ptrs = (q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), _stream())
+    if dropout is None:
+        _check(lib().fmha_varlen_fwd(ctypes.byref(p), *ptrs))
+    else:
+        d = _dropout(dropout)
+        _check(lib().fmha_varlen_fwd_dropout(ctypes.byref(p), ctypes.byref(d), *ptrs))
     del keep
 
 
 def fmha_varlen_bwd(q, k, v, o, d_o, lse, cu_seqlens, max_seqlen, scale, dq, dk, dv, workspace, *,
-                    seqused=None, cu_seqlens_host=None, reuse_schedule=False, only=None):
+                    seqused=None, cu_seqlens_host=None, reuse_schedule=False, only=None, dropout=None):
     """Enqueue the backward pass on torch's current stream; fills dq, dk, dv.
-    `only` = "dq" or "dkv" runs one of the two passes (see the header)."""
+    `only` = "dq" or "dkv" runs one of the two passes (see the header);
+    `dropout` = (p, seed) selects fmha_varlen_bwd_dropout."""
     extra = {None: 0, "dq": FMHA_FLAG_BWD_ONLY_DQ, "dkv": FMHA_FLAG_BWD_ONLY_DKV}[only]
     p, keep = _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_host,
                       reuse_schedule, extra)
     p.q_stride, p.k_stride, p.v_stride, p.o_stride = map(_tok_stride, (q, k, v, o))
     p.do_stride, p.dq_stride, p.dk_stride, p.dv_stride = map(_tok_stride, (d_o, dq, dk, dv))
-    _check(lib().fmha_varlen_bwd(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(),
-                                 o.data_ptr(), d_o.data_ptr(), lse.data_ptr(), dq.data_ptr(),
-                                 dk.data_ptr(), dv.data_ptr(), _stream()))
+    ptrs = (q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
+            dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _stream())
+    if dropout is None:
+        _check(lib().fmha_varlen_bwd(ctypes.byref(p), *ptrs))
+    else:
+        d = _dropout(dropout)
+        _check(lib().fmha_varlen_bwd_dropout(ctypes.byref(p), ctypes.byref(d), *ptrs))
+    del keep
+
+
+def fmha_dropout_keep_mask(heads, cu_seqlens, max_seqlen, dropout, mask, workspace, *, orientation=0,
+                           cu_seqlens_host=None):
+    """Enqueue the kernel that writes the keep mask into `mask` (uint8 [heads, T, row_bytes])."""
+    assert mask.dtype == torch.uint8 and mask.is_contiguous() and mask.dim() == 3 and mask.shape[0] == heads
+    p = Params()
+    p.batch = cu_seqlens.numel() - 1
+    p.total_tokens, p.heads, p.head_dim = mask.shape[1], heads, 64
+    p.max_seqlen = int(max_seqlen)
+    p.dtype = FMHA_F16
+    p.scale = 1.0
+    p.cu_seqlens = cu_seqlens.data_ptr()
+    keep = []
+    if cu_seqlens_host is not None:
+        h = cu_seqlens_host.to(dtype=torch.int32, device="cpu").contiguous()
+        keep.append(h)
+        p.cu_seqlens_host = h.data_ptr()
+    p.workspace = workspace.data_ptr()
+    p.workspace_bytes = workspace.numel() * workspace.element_size()
+    d = _dropout(dropout)
+    _check(lib().fmha_dropout_keep_mask(ctypes.byref(p), ctypes.byref(d), int(orientation),
+                                        mask.shape[2], mask.data_ptr(), _stream()))
     del keep
