@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="only run a plain device-to-device copy of this many MiB a few times "
                          "(reference reading for rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--dropout", type=float, default=0.0, metavar="P",
+                    help="run every step through the dropout entry points with this probability "
+                         "(the headline workload has none; a default run reports p = 0.1 beside it)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
     return ap.parse_args()
@@ -93,6 +96,8 @@ def main():
         return torch.from_numpy(bits.view(np.int16)).cuda().view(dev_dt[dt])
 
     class Dev:
+        drop = (args.dropout, 220808124) if args.dropout > 0 else None   # (p, seed)
+
         def __init__(self, bb):
             self.bb = bb
             self.q, self.k, self.v, self.do = (dev(bb[n]) for n in ("q", "k", "v", "do"))
@@ -106,12 +111,14 @@ def main():
 
         def fwd(self, reuse=False):
             fmha.fmha_varlen_fwd(self.q, self.k, self.v, self.cu, self.bb["max_seqlen"], self.bb["scale"],
-                                 self.o, self.lse, self.ws, seqused=self.su, reuse_schedule=reuse)
+                                 self.o, self.lse, self.ws, seqused=self.su, reuse_schedule=reuse,
+                                 dropout=self.drop)
 
         def bwd(self, only=None):
             fmha.fmha_varlen_bwd(self.q, self.k, self.v, self.o, self.do, self.lse, self.cu,
                                  self.bb["max_seqlen"], self.bb["scale"], self.dq, self.dk, self.dv,
-                                 self.ws, seqused=self.su, reuse_schedule=True, only=only)
+                                 self.ws, seqused=self.su, reuse_schedule=True, only=only,
+                                 dropout=self.drop)
 
         def step(self):
             self.fwd()      # builds the tile list, then the forward kernel
@@ -168,6 +175,16 @@ def main():
 
     ksteps = max(20, min(args.steps, 200))
     k_ms = kernel_times(ksteps)
+    with_dropout = None
+    if args.dropout == 0:
+        # the same cold rotation through the dropout entry points, p = 0.1 (BERT's setting)
+        Dev.drop = (0.1, 220808124)
+        dsec = timed(cold_step, max(20, args.steps // 2), n_sets)
+        dk_ms = kernel_times(max(20, ksteps // 2))
+        Dev.drop = None
+        with_dropout = {"p": 0.1, "ms_per_step": round(dsec * 1e3, 5),
+                        "value": round(fl_all / dsec / 1e12, 3),
+                        "kernels_ms": {k: round(v, 5) for k, v in dk_ms.items()}}
     del sets
     k_fl = {"fmha_fwd_kernel": fl_fwd, "bwd_dq_kernel": fl_dq, "bwd_dkv_kernel": fl_dkv}
     dom = max(k_ms, key=k_ms.get)
@@ -202,6 +219,10 @@ def main():
                   "warm_value": round(fl_all / warm_sec / 1e12, 3)},
         "roofline": roofline,
     }
+    if args.dropout > 0:
+        out["config"]["dropout_p"] = args.dropout
+    if with_dropout:
+        out["with_dropout"] = with_dropout
 
     if not args.no_padded:
         # the same kernels on the padded layout (every sequence 512 rows, keys past the
