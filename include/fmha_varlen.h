@@ -168,6 +168,54 @@ int fmha_varlen_bwd_dropout(const fmha_varlen_params_t* p, const fmha_dropout_t*
 int fmha_dropout_keep_mask(const fmha_varlen_params_t* p, const fmha_dropout_t* dropout,
                            int32_t orientation, int32_t row_bytes, uint8_t* mask, void* stream);
 
+/* ---- Between the padded input format and the unpadded storage -----------------
+ * The paper compresses the [batch, max_seq_len] inputs to the unpadded format with a
+ * gather before the embedding and restores the padded format with a scatter before
+ * the pooler (Section IV-A-1); the positions to keep are where input_mask is non-zero
+ * (nonzero_indices) and the tokens per sequence give batch_offset (Section IV-B-2).
+ * The paper computes nonzero_indices and batch_offset on the CPU, one batch ahead,
+ * because on the GPU the number of valid tokens is not known to the host without a
+ * synchronisation.  Both routes are offered: a host routine, and a device one that
+ * needs no synchronisation because every consumer reads the token count from device
+ * memory (cu_seqlens[batch]) and the caller sizes buffers for the worst case.
+ * The paper does not say what scatter leaves in padding rows: zeros here. */
+
+/* Host arrays in, host arrays out (plain loops, no GPU involved).
+ *   input_mask      : [batch, seqlen] row-major; a token is valid iff its entry is non-zero
+ *   nonzero_indices : batch*seqlen entries of room, or NULL; receives the flat positions
+ *                     b*seqlen+s of the valid tokens in ascending order
+ *   inverse         : batch*seqlen entries, or NULL; receives for every flat position its
+ *                     rank among the valid ones (= its packed row), or -1 for padding
+ *   cu_seqlens      : batch+1 entries; receives the prefix sums of the valid tokens per row
+ *   max_seqlen      : NULL or one entry; receives the largest number of valid tokens in a row */
+int fmha_unpad_indices_host(const int32_t* input_mask, int32_t batch, int32_t seqlen,
+                            int32_t* nonzero_indices, int32_t* inverse, int32_t* cu_seqlens,
+                            int32_t* max_seqlen);
+
+/* The same on the device: all arrays are device memory (inverse may be NULL), sizes as
+ * above; three small launches on `stream`, no host synchronisation.  Entries of
+ * nonzero_indices at and beyond cu_seqlens[batch] are left alone. */
+int fmha_unpad_indices(const int32_t* input_mask, int32_t batch, int32_t seqlen,
+                       int32_t* nonzero_indices, int32_t* inverse, int32_t* cu_seqlens,
+                       void* stream);
+
+/* gather: packed row j <- padded row nonzero_indices[j] for j < *n_rows.
+ *   padded  : device, padded_rows rows of row_bytes bytes (read)
+ *   packed  : device, room for packed_rows rows (written for j < min(*n_rows, packed_rows);
+ *             the rest is left alone)
+ *   n_rows  : device, one int32 - normally cu_seqlens + batch
+ *   row_bytes must be a multiple of 16 and the buffers 16-byte aligned; an index outside
+ *   [0, padded_rows) produces a row of zeros. */
+int fmha_gather_rows(const void* padded, int32_t padded_rows, const int32_t* nonzero_indices,
+                     const int32_t* n_rows, int32_t packed_rows, int64_t row_bytes, void* packed,
+                     void* stream);
+
+/* scatter: padded row r <- packed row inverse[r] if 0 <= inverse[r] < min(*n_rows,
+ * packed_rows), else zeros; all padded_rows rows are written.  Same layout rules as gather. */
+int fmha_scatter_rows(const void* packed, int32_t packed_rows, const int32_t* inverse,
+                      const int32_t* n_rows, int32_t padded_rows, int64_t row_bytes, void* padded,
+                      void* stream);
+
 /* Number of 128-row tiles the schedule holds at most for this shape (host
  * arithmetic), and a device-to-host-free way for tests to locate the tile list
  * inside the workspace: the list starts at byte offset *list_offset and holds

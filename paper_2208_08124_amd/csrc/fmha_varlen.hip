@@ -9,12 +9,13 @@
 #include <cstring>
 
 #include "../../include/fmha_varlen.h"
+#include "host_error.h"
 #include "bwd_kernels.h"
 #include "fwd_kernel.h"
 #include "keep_mask_kernel.h"
 #include "schedule.h"
 
-namespace {
+namespace fmha_host {
 
 thread_local char g_err[512] = "";
 
@@ -25,6 +26,13 @@ int fail(int code, const char* fmt, ...) {
   va_end(ap);
   return code;
 }
+
+}  // namespace fmha_host
+
+namespace {
+
+using fmha_host::fail;
+using fmha_host::g_err;
 
 constexpr size_t kAlign = 256;
 size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -23,6 +23,7 @@ FMHA_FLAG_BWD_ONLY_DKV = 4
 
 EXPORTS = ("fmha_varlen_workspace_size", "fmha_varlen_fwd", "fmha_varlen_bwd",
            "fmha_varlen_fwd_dropout", "fmha_varlen_bwd_dropout", "fmha_dropout_keep_mask",
+           "fmha_unpad_indices_host", "fmha_unpad_indices", "fmha_gather_rows", "fmha_scatter_rows",
            "fmha_varlen_schedule_info", "fmha_last_error")
 
 
@@ -79,6 +80,15 @@ def lib():
         L.fmha_varlen_bwd_dropout.restype = ctypes.c_int
         L.fmha_dropout_keep_mask.argtypes = [ctypes.POINTER(Params), dp, ctypes.c_int32, ctypes.c_int32, vp, vp]
         L.fmha_dropout_keep_mask.restype = ctypes.c_int
+        i32 = ctypes.c_int32
+        L.fmha_unpad_indices_host.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.fmha_unpad_indices_host.restype = ctypes.c_int
+        L.fmha_unpad_indices.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+        L.fmha_unpad_indices.restype = ctypes.c_int
+        L.fmha_gather_rows.argtypes = [vp, i32, vp, vp, i32, ctypes.c_int64, vp, vp]
+        L.fmha_gather_rows.restype = ctypes.c_int
+        L.fmha_scatter_rows.argtypes = [vp, i32, vp, vp, i32, ctypes.c_int64, vp, vp]
+        L.fmha_scatter_rows.restype = ctypes.c_int
         L.fmha_varlen_schedule_info.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_size_t)] * 2
         L.fmha_varlen_schedule_info.restype = ctypes.c_int32
         L.fmha_last_error.restype = ctypes.c_char_p
@@ -217,3 +227,51 @@ def fmha_dropout_keep_mask(heads, cu_seqlens, max_seqlen, dropout, mask, workspa
     _check(lib().fmha_dropout_keep_mask(ctypes.byref(p), ctypes.byref(d), int(orientation),
                                         mask.shape[2], mask.data_ptr(), _stream()))
     del keep
+
+
+def fmha_unpad_indices_host(input_mask):
+    """input_mask: CPU int32 tensor [B, S].  Returns (nonzero_indices [n], inverse [B*S],
+    cu_seqlens [B+1], max_seqlen) computed by the library's host routine."""
+    m = input_mask.to(dtype=torch.int32, device="cpu").contiguous()
+    nb, s = m.shape
+    idx = torch.empty(nb * s, dtype=torch.int32)
+    inv = torch.empty(nb * s, dtype=torch.int32)
+    cu = torch.empty(nb + 1, dtype=torch.int32)
+    mx = ctypes.c_int32(0)
+    _check(lib().fmha_unpad_indices_host(m.data_ptr(), nb, s, idx.data_ptr(), inv.data_ptr(), cu.data_ptr(),
+                                         ctypes.addressof(mx)))
+    return idx[:int(cu[-1])], inv, cu, int(mx.value)
+
+
+def fmha_unpad_indices(input_mask, nonzero_indices, inverse, cu_seqlens):
+    """Device version: input_mask int32 [B, S] on the GPU; fills the three device arrays."""
+    nb, s = input_mask.shape
+    assert input_mask.dtype == torch.int32 and input_mask.is_cuda and input_mask.is_contiguous()
+    assert nonzero_indices.numel() >= nb * s and cu_seqlens.numel() == nb + 1
+    assert inverse is None or inverse.numel() == nb * s
+    _check(lib().fmha_unpad_indices(input_mask.data_ptr(), nb, s, nonzero_indices.data_ptr(),
+                                    None if inverse is None else inverse.data_ptr(),
+                                    cu_seqlens.data_ptr(), _stream()))
+
+
+def _rows(t):
+    assert t.is_cuda and t.is_contiguous() and t.dim() >= 2
+    return t.shape[0], (t.numel() // max(t.shape[0], 1)) * t.element_size()
+
+
+def fmha_gather_rows(padded, nonzero_indices, n_rows, packed):
+    """packed[j] = padded[nonzero_indices[j]] for j < n_rows[0] (a device int32)."""
+    pr, rb = _rows(padded)
+    kr, rb2 = _rows(packed)
+    assert rb == rb2 or kr == 0 or pr == 0
+    _check(lib().fmha_gather_rows(padded.data_ptr(), pr, nonzero_indices.data_ptr(), n_rows.data_ptr(),
+                                  kr, rb if pr else rb2, packed.data_ptr(), _stream()))
+
+
+def fmha_scatter_rows(packed, inverse, n_rows, padded):
+    """padded[r] = packed[inverse[r]] where that is a valid packed row, zeros elsewhere."""
+    kr, rb = _rows(packed)
+    pr, rb2 = _rows(padded)
+    assert rb == rb2 or kr == 0 or pr == 0
+    _check(lib().fmha_scatter_rows(packed.data_ptr(), kr, inverse.data_ptr(), n_rows.data_ptr(),
+                                   pr, rb2 if pr else rb, padded.data_ptr(), _stream()))
