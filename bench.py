@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--dropout", type=float, default=0.0, metavar="P",
                     help="run every step through the dropout entry points with this probability "
                          "(the headline workload has none; a default run reports p = 0.1 beside it)")
+    ap.add_argument("--op", choices=["attention", "unpad"], default="attention",
+                    help="attention (the headline path) or the padded <-> unpadded row copies")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
     return ap.parse_args()
@@ -76,6 +78,9 @@ def main():
         print(json.dumps({"copy_calibration_bytes": n, "copies": 5}))
         return
     dev_dt = {"f16": torch.float16, "bf16": torch.bfloat16}
+    if args.op == "unpad":
+        bench_unpad(args, torch, fmha, wl)
+        return
 
     b = wl.make_workload(args.config, backward=True)
     if args.uniform:
@@ -257,6 +262,91 @@ def main():
                                "cores": oracle.num_threads(), "kind": "oracle",
                                "sample": "%d of %d sequences, all heads, fwd+bwd, %.2f s" % (len(pick), n, csec)}
 
+    print(json.dumps(out))
+
+
+def bench_unpad(args, torch, fmha, wl):
+    """The steps either side of the attention path: input_mask -> nonzero_indices / batch_offset,
+    gather (padded -> unpadded) and scatter (back), on hidden-state rows of the workload's
+    batch: [B, max_seqlen, H*64] 16-bit.  Bound by HBM traffic; a step = indices + one gather
+    + one scatter, rotating over buffer sets like the attention bench."""
+    w = wl.WORKLOADS[args.config]
+    b = wl.make_workload(args.config, backward=False)
+    lengths = b["lengths"]
+    nb, s, hid = int(b["batch"]), int(b["max_seqlen"]), int(b["heads"]) * 64
+    rows, t = nb * s, int(b["total_tokens"])
+    row_bytes = hid * 2
+    mask_np = (np.arange(s)[None, :] < lengths[:, None]).astype(np.int32)
+    n_sets = max(2, min(8, -(-(1 << 30) // (3 * rows * row_bytes)) + 1))
+
+    class Set:
+        def __init__(self):
+            self.mask = torch.from_numpy(mask_np).cuda()
+            self.x = torch.randint(-30000, 30000, (rows, hid), dtype=torch.int16, device="cuda")
+            self.packed = torch.empty((rows, hid), dtype=torch.int16, device="cuda")   # worst-case room
+            self.back = torch.empty((rows, hid), dtype=torch.int16, device="cuda")
+            self.idx = torch.empty(rows, dtype=torch.int32, device="cuda")
+            self.inv = torch.empty(rows, dtype=torch.int32, device="cuda")
+            self.cu = torch.empty(nb + 1, dtype=torch.int32, device="cuda")
+
+        def indices(self):
+            fmha.fmha_unpad_indices(self.mask, self.idx, self.inv, self.cu)
+
+        def gather(self):
+            fmha.fmha_gather_rows(self.x, self.idx, self.cu[-1:], self.packed)
+
+        def scatter(self):
+            fmha.fmha_scatter_rows(self.packed, self.inv, self.cu[-1:], self.back)
+
+    sets = [Set() for _ in range(n_sets)]
+    names = ("unpad_indices", "gather_rows", "scatter_rows")
+    for x in sets:
+        x.indices(); x.gather(); x.scatter()
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        for x in sets:
+            x.indices(); x.gather(); x.scatter()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        x = sets[i % n_sets]
+        x.indices(); x.gather(); x.scatter()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        x = sets[i % n_sets]
+        evs[i][0].record(); x.indices(); evs[i][1].record(); x.gather(); evs[i][2].record(); x.scatter(); evs[i][3].record()
+    torch.cuda.synchronize()
+    k_ms = {nm: sum(e[j].elapsed_time(e[j + 1]) for e in evs) / args.steps for j, nm in enumerate(names)}
+    alg = {"unpad_indices": 2 * rows * 4 + (rows + t) * 4 + (nb + 1) * 4,          # mask twice, inverse, indices, offsets
+           "gather_rows": 2 * t * row_bytes + t * 4,
+           "scatter_rows": t * row_bytes + rows * row_bytes + rows * 4}
+    dom = max(k_ms, key=k_ms.get)
+    gbs = {k: alg[k] / (k_ms[k] * 1e-3) / 1e9 for k in names}
+    out = {"metric": "padded <-> unpadded rows, algorithmic GB/s (indices + gather + scatter)",
+           "value": round(sum(alg.values()) / sec / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 5),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u16", "data": "synthetic",
+           "config": {"workload": w.name + "_hidden_rows", "baseline_config": args.config, "sequences": nb,
+                      "max_seqlen": s, "row_bytes": row_bytes, "valid_rows": t, "padded_rows": rows,
+                      "buffer_sets": n_sets},
+           "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(gbs[dom], 1), "peak": HBM_GBS,
+                        "unit": "GB/s", "frac": round(gbs[dom] / HBM_GBS, 4), "traffic": None,
+                        "avg_launch_ms": round(k_ms[dom], 5),
+                        "kernels_ms": {k: round(v, 5) for k, v in k_ms.items()},
+                        "kernels_GBs": {k: round(v, 1) for k, v in gbs.items()},
+                        "algorithmic_bytes": alg}}
+    if not args.no_cpu_baseline:
+        from oracle import unpad
+        xs = np.random.default_rng(0).integers(0, 65535, size=(rows, hid)).astype(np.uint16)
+        t0 = time.perf_counter()
+        idx, inv, cu = unpad.unpad_indices(mask_np)
+        g = unpad.gather_rows(xs, idx)
+        unpad.scatter_rows(g, idx, rows)
+        csec = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(sum(alg.values()) / csec / 1e9, 4), "unit": "GB/s", "cores": 1,
+                               "kind": "oracle", "sample": "the whole batch once, %.2f s" % csec}
     print(json.dumps(out))
 
 

@@ -32,7 +32,7 @@ int check_rows(const void* src, const void* dst, const int32_t* map, const int32
 }
 
 unsigned copy_grid(int64_t rows, int64_t chunks) {
-  const int64_t want = (rows * chunks + 255) / 256;
+  const int64_t want = (rows * chunks + 1023) / 1024;  // four pieces per thread and trip
   const int64_t cap = 256 * 16;  // 16 workgroups per compute unit keep every memory channel busy
   return (unsigned)(want < 1 ? 1 : (want > cap ? cap : want));
 }

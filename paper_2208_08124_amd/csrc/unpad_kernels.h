@@ -82,12 +82,26 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restric
                                                           int chunks, int dst_rows, uint4* __restrict__ dst) {
   const int n = min(max(*n_rows, 0), dst_rows);
   const int64_t total = (int64_t)n * chunks;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-    const int j = (int)(i / chunks), c = (int)(i - (int64_t)j * chunks);
-    const int r = idx[j];
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (r >= 0 && r < src_rows) v = src[(int64_t)r * chunks + c];
-    dst[i] = v;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  // four independent 16-byte pieces per thread and trip: all loads are issued before
+  // the first store, which keeps enough bytes in flight to cover the HBM latency
+  for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < total; i0 += 4 * stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const int64_t i = i0 + u * stride;
+      v[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (i < total) {
+        const int j = (int)(i / chunks), c = (int)(i - (int64_t)j * chunks);
+        const int r = idx[j];
+        if (r >= 0 && r < src_rows) v[u] = src[(int64_t)r * chunks + c];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const int64_t i = i0 + u * stride;
+      if (i < total) dst[i] = v[u];
+    }
   }
 }
 
@@ -99,12 +113,24 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restri
                                                            int chunks, int dst_rows, uint4* __restrict__ dst) {
   const int n = min(max(*n_rows, 0), src_rows);
   const int64_t total = (int64_t)dst_rows * chunks;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
-    const int r = (int)(i / chunks), c = (int)(i - (int64_t)r * chunks);
-    const int j = inverse[r];
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (j >= 0 && j < n) v = src[(int64_t)j * chunks + c];
-    dst[i] = v;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i0 < total; i0 += 4 * stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const int64_t i = i0 + u * stride;
+      v[u] = make_uint4(0u, 0u, 0u, 0u);
+      if (i < total) {
+        const int r = (int)(i / chunks), c = (int)(i - (int64_t)r * chunks);
+        const int j = inverse[r];
+        if (j >= 0 && j < n) v[u] = src[(int64_t)j * chunks + c];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      const int64_t i = i0 + u * stride;
+      if (i < total) dst[i] = v[u];
+    }
   }
 }
 
