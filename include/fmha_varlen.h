@@ -216,6 +216,48 @@ int fmha_scatter_rows(const void* packed, int32_t packed_rows, const int32_t* in
                       const int32_t* n_rows, int32_t padded_rows, int64_t row_bytes, void* padded,
                       void* stream);
 
+/* ---- Dropout + Add + LayerNorm on the packed rows ---------------------------
+ * The paper fuses the Dropout, Add and LayerNorm operators of the encoder into one
+ * forward and two backward kernels (Section IV-C-1) and gives no formulas; these are
+ * the operators' definitions, per row of the [rows, hidden] hidden states:
+ *   forward   z = dropout(x) + residual,  mu = mean(z),  rstd = 1 / sqrt(var(z) + eps)
+ *             (biased variance),  y = (z - mu) rstd gamma + beta
+ *   backward  g = dy gamma,  xh = (z - mu) rstd,
+ *             dz = rstd (g - mean(g) - xh mean(g xh)),  dresidual = dz,  dx = dropout'(dz),
+ *             dgamma = sum over rows of dy xh,  dbeta = sum over rows of dy
+ * dropout(x) = x o M / (1 - p') with p' = round(256 p) / 256 and the mask regenerated
+ * from the seed in both directions: element (row t, column c) is kept iff byte c & 15
+ * (byte c & 3 of output word (c >> 2) & 3) of the Philox4x32-10 call with counter words
+ * (c >> 4, t, 0x4C4E, 0) and key words (seed & 0xffffffff, seed >> 32) is >= round(256 p).
+ * x, residual, y, z, dy, dx, dresidual are [rows, hidden] 16-bit (dtype), dense rows;
+ * gamma, beta, dgamma, dbeta are fp32 [hidden]; mu, rstd fp32 [rows].  Arithmetic in
+ * fp32; z is stored rounded to 16 bits and the backward works from that stored z. */
+typedef struct fmha_ln_params {
+  int32_t rows;          /* rows the buffers hold (T, or the worst case batch * max_seq_len) */
+  int32_t hidden;        /* multiple of 16, at most 4096 */
+  int32_t dtype;         /* fmha_dtype_t */
+  float eps;             /* >= 0 */
+  const int32_t* n_rows; /* optional device int32: rows actually present (clamped to [0, rows]),
+                            e.g. cu_seqlens + batch; rows beyond it are neither read nor written */
+  fmha_dropout_t dropout; /* p = 0: no dropout */
+} fmha_ln_params_t;
+
+/* Forward; y, z, mu, rstd are written, everything else read.  One launch. */
+int fmha_dropout_add_ln_fwd(const fmha_ln_params_t* p, const void* x, const void* residual,
+                            const float* gamma, const float* beta, void* y, void* z, float* mu,
+                            float* rstd, void* stream);
+
+/* Bytes of device workspace the backward needs (per-workgroup column sums); 0 on invalid sizes. */
+size_t fmha_dropout_add_ln_bwd_workspace_size(int32_t rows, int32_t hidden);
+
+/* Backward; z, mu, rstd are the forward's outputs; dx, dgamma, dbeta are written, and
+ * dresidual unless it is NULL (without dropout it equals dx).  Two launches; the column
+ * sums are added in a fixed order, so results are reproducible run to run. */
+int fmha_dropout_add_ln_bwd(const fmha_ln_params_t* p, const void* dy, const void* z, const float* mu,
+                            const float* rstd, const float* gamma, void* dx, void* dresidual,
+                            float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
 /* Number of 128-row tiles the schedule holds at most for this shape (host
  * arithmetic), and a device-to-host-free way for tests to locate the tile list
  * inside the workspace: the list starts at byte offset *list_offset and holds

@@ -24,6 +24,7 @@ FMHA_FLAG_BWD_ONLY_DKV = 4
 EXPORTS = ("fmha_varlen_workspace_size", "fmha_varlen_fwd", "fmha_varlen_bwd",
            "fmha_varlen_fwd_dropout", "fmha_varlen_bwd_dropout", "fmha_dropout_keep_mask",
            "fmha_unpad_indices_host", "fmha_unpad_indices", "fmha_gather_rows", "fmha_scatter_rows",
+           "fmha_dropout_add_ln_fwd", "fmha_dropout_add_ln_bwd", "fmha_dropout_add_ln_bwd_workspace_size",
            "fmha_varlen_schedule_info", "fmha_last_error")
 
 
@@ -46,6 +47,12 @@ class Params(ctypes.Structure):
 class Dropout(ctypes.Structure):
     """Mirror of fmha_dropout_t."""
     _fields_ = [("p", ctypes.c_float), ("seed", ctypes.c_uint64)]
+
+
+class LnParams(ctypes.Structure):
+    """Mirror of fmha_ln_params_t."""
+    _fields_ = [("rows", ctypes.c_int32), ("hidden", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("eps", ctypes.c_float), ("n_rows", ctypes.c_void_p), ("dropout", Dropout)]
 
 
 class FmhaError(RuntimeError):
@@ -89,6 +96,13 @@ def lib():
         L.fmha_gather_rows.restype = ctypes.c_int
         L.fmha_scatter_rows.argtypes = [vp, i32, vp, vp, i32, ctypes.c_int64, vp, vp]
         L.fmha_scatter_rows.restype = ctypes.c_int
+        lp = ctypes.POINTER(LnParams)
+        L.fmha_dropout_add_ln_fwd.argtypes = [lp] + [vp] * 9
+        L.fmha_dropout_add_ln_fwd.restype = ctypes.c_int
+        L.fmha_dropout_add_ln_bwd.argtypes = [lp] + [vp] * 10 + [ctypes.c_size_t, vp]
+        L.fmha_dropout_add_ln_bwd.restype = ctypes.c_int
+        L.fmha_dropout_add_ln_bwd_workspace_size.argtypes = [i32, i32]
+        L.fmha_dropout_add_ln_bwd_workspace_size.restype = ctypes.c_size_t
         L.fmha_varlen_schedule_info.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_size_t)] * 2
         L.fmha_varlen_schedule_info.restype = ctypes.c_int32
         L.fmha_last_error.restype = ctypes.c_char_p
@@ -275,3 +289,43 @@ def fmha_scatter_rows(packed, inverse, n_rows, padded):
     assert rb == rb2 or kr == 0 or pr == 0
     _check(lib().fmha_scatter_rows(packed.data_ptr(), kr, inverse.data_ptr(), n_rows.data_ptr(),
                                    pr, rb2 if pr else rb, padded.data_ptr(), _stream()))
+
+
+def _ln_params(t, eps, dropout, n_rows):
+    assert t.dim() == 2 and t.is_contiguous() and t.is_cuda
+    p = LnParams()
+    p.rows, p.hidden = t.shape
+    p.dtype = _dtype_code(t)
+    p.eps = float(eps)
+    if n_rows is not None:
+        assert n_rows.dtype == torch.int32 and n_rows.is_cuda
+        p.n_rows = n_rows.data_ptr()
+    p.dropout = _dropout(dropout) if dropout is not None else Dropout(0.0, 0)
+    return p
+
+
+def fmha_dropout_add_ln_bwd_workspace_size(rows: int, hidden: int) -> int:
+    return int(lib().fmha_dropout_add_ln_bwd_workspace_size(rows, hidden))
+
+
+def fmha_dropout_add_ln_fwd(x, residual, gamma, beta, eps, y, z, mu, rstd, *, dropout=None, n_rows=None):
+    """y = LayerNorm(dropout(x) + residual) on [rows, hidden] 16-bit tensors; fills y, z, mu, rstd."""
+    p = _ln_params(x, eps, dropout, n_rows)
+    for t in (residual, y, z):
+        assert t.shape == x.shape and t.dtype == x.dtype and t.is_contiguous()
+    for t in (gamma, beta, mu, rstd):
+        assert t.dtype == torch.float32 and t.is_contiguous()
+    _check(lib().fmha_dropout_add_ln_fwd(ctypes.byref(p), x.data_ptr(), residual.data_ptr(), gamma.data_ptr(),
+                                         beta.data_ptr(), y.data_ptr(), z.data_ptr(), mu.data_ptr(),
+                                         rstd.data_ptr(), _stream()))
+
+
+def fmha_dropout_add_ln_bwd(dy, z, mu, rstd, gamma, eps, dx, dresidual, dgamma, dbeta, workspace, *,
+                            dropout=None, n_rows=None):
+    """Backward of fmha_dropout_add_ln_fwd; fills dx, dresidual (unless None), dgamma, dbeta."""
+    p = _ln_params(dy, eps, dropout, n_rows)
+    _check(lib().fmha_dropout_add_ln_bwd(ctypes.byref(p), dy.data_ptr(), z.data_ptr(), mu.data_ptr(),
+                                         rstd.data_ptr(), gamma.data_ptr(), dx.data_ptr(),
+                                         None if dresidual is None else dresidual.data_ptr(),
+                                         dgamma.data_ptr(), dbeta.data_ptr(), workspace.data_ptr(),
+                                         workspace.numel() * workspace.element_size(), _stream()))
