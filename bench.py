@@ -44,8 +44,9 @@ def parse():
     ap.add_argument("--dropout", type=float, default=0.0, metavar="P",
                     help="run every step through the dropout entry points with this probability "
                          "(the headline workload has none; a default run reports p = 0.1 beside it)")
-    ap.add_argument("--op", choices=["attention", "unpad"], default="attention",
-                    help="attention (the headline path) or the padded <-> unpadded row copies")
+    ap.add_argument("--op", choices=["attention", "unpad", "layernorm"], default="attention",
+                    help="attention (the headline path), the padded <-> unpadded row copies, or "
+                         "Dropout+Add+LayerNorm on the packed rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
     return ap.parse_args()
@@ -80,6 +81,9 @@ def main():
     dev_dt = {"f16": torch.float16, "bf16": torch.bfloat16}
     if args.op == "unpad":
         bench_unpad(args, torch, fmha, wl)
+        return
+    if args.op == "layernorm":
+        bench_layernorm(args, torch, fmha, wl)
         return
 
     b = wl.make_workload(args.config, backward=True)
@@ -347,6 +351,87 @@ def bench_unpad(args, torch, fmha, wl):
         csec = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(sum(alg.values()) / csec / 1e9, 4), "unit": "GB/s", "cores": 1,
                                "kind": "oracle", "sample": "the whole batch once, %.2f s" % csec}
+    print(json.dumps(out))
+
+
+def bench_layernorm(args, torch, fmha, wl):
+    """Dropout + Add + LayerNorm, forward and backward, on the packed hidden states of the
+    workload's batch ([T, H*64] 16-bit, p = --dropout or 0.1).  Bound by HBM traffic; a step =
+    forward + backward, rotating over buffer sets like the attention bench."""
+    w = wl.WORKLOADS[args.config]
+    b = wl.make_workload(args.config, backward=False)
+    t, hid = int(b["total_tokens"]), int(b["heads"]) * 64
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[w.dtype]
+    p = args.dropout if args.dropout > 0 else 0.1
+    drop = (p, 220808124)
+    n_sets = max(2, min(8, -(-(1 << 30) // (8 * t * hid * 2)) + 1))
+    ws_bytes = fmha.fmha_dropout_add_ln_bwd_workspace_size(t, hid)
+
+    class Set:
+        def __init__(self):
+            g = lambda: torch.randn((t, hid), dtype=torch.float32, device="cuda").to(tdt)
+            self.x, self.r, self.dy = g(), g(), g()
+            self.y, self.z, self.dx, self.dr = (torch.empty((t, hid), dtype=tdt, device="cuda") for _ in range(4))
+            self.mu, self.rstd = (torch.empty(t, dtype=torch.float32, device="cuda") for _ in range(2))
+            self.gamma = 1 + 0.1 * torch.randn(hid, dtype=torch.float32, device="cuda")
+            self.beta = 0.1 * torch.randn(hid, dtype=torch.float32, device="cuda")
+            self.dgamma, self.dbeta = (torch.empty(hid, dtype=torch.float32, device="cuda") for _ in range(2))
+            self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+        def fwd(self):
+            fmha.fmha_dropout_add_ln_fwd(self.x, self.r, self.gamma, self.beta, 1e-12, self.y, self.z, self.mu,
+                                         self.rstd, dropout=drop)
+
+        def bwd(self):
+            fmha.fmha_dropout_add_ln_bwd(self.dy, self.z, self.mu, self.rstd, self.gamma, 1e-12, self.dx, self.dr,
+                                         self.dgamma, self.dbeta, self.ws, dropout=drop)
+
+    sets = [Set() for _ in range(n_sets)]
+    for _ in range(max(1, args.warmup // n_sets)):
+        for x in sets:
+            x.fwd(); x.bwd()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        x = sets[i % n_sets]
+        x.fwd(); x.bwd()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        x = sets[i % n_sets]
+        evs[i][0].record(); x.fwd(); evs[i][1].record(); x.bwd(); evs[i][2].record()
+    torch.cuda.synchronize()
+    names = ("ln_fwd_kernel", "ln_bwd (rows + columns)")
+    k_ms = {nm: sum(e[j].elapsed_time(e[j + 1]) for e in evs) / args.steps for j, nm in enumerate(names)}
+    row = hid * 2
+    alg = {names[0]: t * (4 * row + 8) + 8 * hid,                       # x, r in; y, z out; mu, rstd; gamma, beta
+           names[1]: t * (4 * row + 8) + 12 * hid + 2 * ws_bytes}       # dy, z in; dx, dr out; column sums out and in
+    dom = max(k_ms, key=k_ms.get)
+    gbs = {k: alg[k] / (k_ms[k] * 1e-3) / 1e9 for k in names}
+    out = {"metric": "Dropout+Add+LayerNorm fwd+bwd, algorithmic GB/s",
+           "value": round(sum(alg.values()) / sec / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 5),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": w.name + "_hidden_rows", "baseline_config": args.config, "rows": t,
+                      "hidden": hid, "storage": w.dtype, "dropout_p": p, "buffer_sets": n_sets},
+           "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(gbs[dom], 1), "peak": HBM_GBS,
+                        "unit": "GB/s", "frac": round(gbs[dom] / HBM_GBS, 4), "traffic": None,
+                        "avg_launch_ms": round(k_ms[dom], 5),
+                        "kernels_ms": {k: round(v, 5) for k, v in k_ms.items()},
+                        "kernels_GBs": {k: round(v, 1) for k, v in gbs.items()},
+                        "algorithmic_bytes": alg}}
+    if not args.no_cpu_baseline:
+        from oracle import layernorm as oln
+        n = min(t, 4096)
+        f = lambda a: a[:n].double().cpu().numpy()
+        x0 = sets[0]
+        t0 = time.perf_counter()
+        oln.fwd(f(x0.x), f(x0.r), x0.gamma.cpu().numpy(), x0.beta.cpu().numpy(), 1e-12)
+        oln.bwd(f(x0.dy), f(x0.x), f(x0.r), x0.gamma.cpu().numpy(), 1e-12)
+        csec = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(sum(alg.values()) * n / t / csec / 1e9, 4), "unit": "GB/s", "cores": 1,
+                               "kind": "oracle", "sample": "%d of %d rows, no dropout, fwd+bwd, %.2f s" % (n, t, csec)}
     print(json.dumps(out))
 
 

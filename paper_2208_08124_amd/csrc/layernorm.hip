@@ -153,7 +153,7 @@ int fmha_dropout_add_ln_bwd(const fmha_ln_params_t* p, const void* dy, const voi
         : launch_bwd<__bf16, 4>(a, grid, st, dy, z, mu, rstd, gamma, dx, dresidual, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FMHA_ERR_HIP, "LayerNorm backward launch failed: %s", hipGetErrorString(e));
-  fmha::ln_bwd_cols_kernel<<<dim3((unsigned)((a.hidden + 63) / 64), 2), 256, 0, st>>>(partial, (int)grid, a.hidden, dgamma, dbeta);
+  fmha::ln_bwd_cols_kernel<<<dim3((unsigned)((a.hidden + 63) / 64), 2), fmha::kLnColsThreads, 0, st>>>(partial, (int)grid, a.hidden, dgamma, dbeta);
   e = hipGetLastError();
   if (e != hipSuccess) return fail(FMHA_ERR_HIP, "LayerNorm column-sum launch failed: %s", hipGetErrorString(e));
   return FMHA_OK;

@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kLnBwdThreads / CPL) void ln_bwd_rows_kernel(const 
                                                                     const float* __restrict__ gamma,
                                                                     uint16_t* __restrict__ dx, uint16_t* __restrict__ dr,
                                                                     float* __restrict__ partial) {
-  __shared__ float colsum[1024 * CPL];
+  __shared__ __align__(16) float colsum[(kLnBwdThreads / CPL / 64 / 2) * 1024 * CPL];  // 32 KB
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int n = a.hidden, rows = ln_rows(a);
   const float inv_n = 1.f / (float)n;
@@ -237,47 +237,90 @@ __global__ __launch_bounds__(kLnBwdThreads / CPL) void ln_bwd_rows_kernel(const 
     }
   }
 
-  // column sums over the workgroup's wavefronts, one after the other (a fixed order:
-  // results do not change from run to run), first for dgamma, then for dbeta
+  // Column sums over the workgroup's wavefronts by halving: the upper half of the live
+  // wavefronts hands its sums over through LDS, the lower half adds them, until wavefront 0
+  // holds the total.  A fixed tree: results do not change from run to run.
 #pragma unroll
   for (int which = 0; which < 2; which++) {
-    for (int w = 0; w < kWaves; w++) {
-      if (wave == w) {
+    float(&acc)[CPL][16] = which == 0 ? acc_g : acc_b;
+    for (int half = kWaves / 2; half >= 1; half >>= 1) {
+      if (wave >= half && wave < 2 * half) {
 #pragma unroll
         for (int i = 0; i < CPL; i++) {
           const int ci = lane + 64 * i;
           if (16 * ci < n) {
+            float* s = &colsum[(wave - half) * (1024 * CPL) + 16 * ci];
 #pragma unroll
-            for (int k = 0; k < 16; k++) {
-              const float v = which == 0 ? acc_g[i][k] : acc_b[i][k];
-              float* s = &colsum[16 * ci + k];
-              *s = w == 0 ? v : *s + v;
+            for (int k4 = 0; k4 < 4; k4++)
+              *reinterpret_cast<float4*>(s + 4 * k4) =
+                  make_float4(acc[i][4 * k4], acc[i][4 * k4 + 1], acc[i][4 * k4 + 2], acc[i][4 * k4 + 3]);
+          }
+        }
+      }
+      __syncthreads();
+      if (wave < half) {
+#pragma unroll
+        for (int i = 0; i < CPL; i++) {
+          const int ci = lane + 64 * i;
+          if (16 * ci < n) {
+            const float* s = &colsum[wave * (1024 * CPL) + 16 * ci];
+#pragma unroll
+            for (int k4 = 0; k4 < 4; k4++) {
+              const float4 v = *reinterpret_cast<const float4*>(s + 4 * k4);
+              acc[i][4 * k4] += v.x, acc[i][4 * k4 + 1] += v.y, acc[i][4 * k4 + 2] += v.z, acc[i][4 * k4 + 3] += v.w;
             }
           }
         }
       }
       __syncthreads();
     }
-    float* out = partial + ((int64_t)blockIdx.x * 2 + which) * n;
-    for (int c = threadIdx.x; c < n; c += kThreadsHere) out[c] = colsum[c];
-    __syncthreads();
+    if (wave == 0) {
+      float* out = partial + ((int64_t)blockIdx.x * 2 + which) * n;
+#pragma unroll
+      for (int i = 0; i < CPL; i++) {
+        const int ci = lane + 64 * i;
+        if (16 * ci < n) {
+#pragma unroll
+          for (int k4 = 0; k4 < 4; k4++)
+            *reinterpret_cast<float4*>(out + 16 * ci + 4 * k4) =
+                make_float4(acc[i][4 * k4], acc[i][4 * k4 + 1], acc[i][4 * k4 + 2], acc[i][4 * k4 + 3]);
+        }
+      }
+    }
   }
 }
 
 // Backward, kernel 2 of 2: dgamma, dbeta <- sums of the workgroups' partial column sums.
-// One workgroup per 64 columns and output; its 4 wavefronts split the partial rows.
-__global__ __launch_bounds__(256) void ln_bwd_cols_kernel(const float* __restrict__ partial, int n_partial, int n,
-                                                          float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  __shared__ float part[4][64];
+// One workgroup per 64 columns and output; its 16 wavefronts split the partial rows (four
+// independent running sums each, so that the loads overlap), then combine in a fixed order.
+constexpr int kLnColsThreads = 1024;
+__global__ __launch_bounds__(kLnColsThreads) void ln_bwd_cols_kernel(const float* __restrict__ partial, int n_partial,
+                                                                     int n, float* __restrict__ dgamma,
+                                                                     float* __restrict__ dbeta) {
+  constexpr int kWaves = kLnColsThreads / 64;
+  __shared__ float part[kWaves][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int which = blockIdx.y;
   const int c = blockIdx.x * 64 + lane;
-  float s = 0.f;
-  if (c < n)
-    for (int b = wave; b < n_partial; b += 4) s += partial[((int64_t)b * 2 + which) * n + c];
-  part[wave][lane] = s;
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+  if (c < n) {
+    const float* p = partial + (int64_t)which * n + c;
+    const int64_t step = 2 * (int64_t)n;
+    int b = wave;
+    for (; b + 3 * kWaves < n_partial; b += 4 * kWaves) {
+#pragma unroll
+      for (int u = 0; u < 4; u++) s[u] += p[(int64_t)(b + u * kWaves) * step];
+    }
+    for (; b < n_partial; b += kWaves) s[0] += p[(int64_t)b * step];
+  }
+  part[wave][lane] = (s[0] + s[1]) + (s[2] + s[3]);
   __syncthreads();
-  if (wave == 0 && c < n) (which == 0 ? dgamma : dbeta)[c] = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+  if (wave == 0 && c < n) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; w++) t += part[w][lane];
+    (which == 0 ? dgamma : dbeta)[c] = t;
+  }
 }
 
 }  // namespace fmha
