@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--dropout", type=float, default=0.0, metavar="P",
                     help="run every step through the dropout entry points with this probability "
                          "(the headline workload has none; a default run reports p = 0.1 beside it)")
-    ap.add_argument("--op", choices=["attention", "unpad", "layernorm"], default="attention",
+    ap.add_argument("--op", choices=["attention", "unpad", "layernorm", "embedding"], default="attention",
                     help="attention (the headline path), the padded <-> unpadded row copies, or "
                          "Dropout+Add+LayerNorm on the packed rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -84,6 +84,9 @@ def main():
         return
     if args.op == "layernorm":
         bench_layernorm(args, torch, fmha, wl)
+        return
+    if args.op == "embedding":
+        bench_embedding(args, torch, fmha, wl)
         return
 
     b = wl.make_workload(args.config, backward=True)
@@ -432,6 +435,77 @@ def bench_layernorm(args, torch, fmha, wl):
         csec = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(sum(alg.values()) * n / t / csec / 1e9, 4), "unit": "GB/s", "cores": 1,
                                "kind": "oracle", "sample": "%d of %d rows, no dropout, fwd+bwd, %.2f s" % (n, t, csec)}
+    print(json.dumps(out))
+
+
+def bench_embedding(args, torch, fmha, wl):
+    """Embedding backward on the workload's token count: T gradient rows of H*64 16-bit values
+    scattered onto a 30 522-row weight gradient (BERT's word-piece vocabulary) with Zipf-distributed
+    ids.  A step = one accumulation into an already cleared weight gradient; both work splits are
+    timed; the roofline entry prices the default (die-aware) one against HBM traffic."""
+    w = wl.WORKLOADS[args.config]
+    b = wl.make_workload(args.config, backward=False)
+    t, hid, vocab = int(b["total_tokens"]), int(b["heads"]) * 64, 30522
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[w.dtype]
+    ids_np = wl.zipf_token_ids(t, vocab, w.seed + 100)
+    distinct = int(np.unique(ids_np).size)
+    top = int(np.bincount(ids_np).max())
+    n_sets = max(2, min(8, -(-(1 << 30) // (t * hid * 2 + vocab * hid * 2)) + 1))
+
+    class Set:
+        def __init__(self):
+            self.dy = torch.randn((t, hid), dtype=torch.float32, device="cuda").to(tdt)
+            self.ids = torch.from_numpy(ids_np).cuda()
+            self.dw = torch.zeros((vocab, hid), dtype=tdt, device="cuda")
+
+    sets = [Set() for _ in range(n_sets)]
+
+    def timed_events(plain, no_die=False):
+        for x in sets:
+            fmha.fmha_embedding_bwd(x.dy, x.ids, x.dw, plain_split=plain, no_die_split=no_die)
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        for i in range(args.steps):
+            x = sets[i % n_sets]
+            evs[i][0].record()
+            fmha.fmha_embedding_bwd(x.dy, x.ids, x.dw, plain_split=plain, no_die_split=no_die)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        return sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+
+    ms_die, ms_plain, ms_nodie = timed_events(False), timed_events(True), timed_events(False, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        x = sets[i % n_sets]
+        fmha.fmha_embedding_bwd(x.dy, x.ids, x.dw)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    row = hid * 2
+    alg = t * row + t * 4 + 2 * distinct * row     # gradient rows in, ids, one read-modify-write per touched weight row
+    out = {"metric": "embedding backward, gradient rows per second", "value": round(t / sec, 1), "unit": "rows/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 5),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+           "config": {"workload": w.name + "_token_ids", "baseline_config": args.config, "rows": t, "hidden": hid,
+                      "vocab": vocab, "ids": "Zipf(1.0), seeded", "distinct_ids": distinct,
+                      "most_frequent_id_count": top, "buffer_sets": n_sets},
+           "roofline": {"bound": "hbm", "kernel": "embedding_bwd_window_kernel",
+                        "achieved": round(alg / (ms_die * 1e-3) / 1e9, 1), "peak": HBM_GBS, "unit": "GB/s",
+                        "frac": round(alg / (ms_die * 1e-3) / 1e9 / HBM_GBS, 4), "traffic": None,
+                        "avg_launch_ms": round(ms_die, 5), "algorithmic_bytes": alg,
+                        "kernels_ms": {"embedding_bwd_window_kernel (default: duplicates merged, split by die)": round(ms_die, 5),
+                                       "embedding_bwd_window_kernel (duplicates merged, no die split)": round(ms_nodie, 5),
+                                       "embedding_bwd_kernel (plain: one token per wavefront)": round(ms_plain, 5)},
+                        "packed_atomics_per_s": round(t * hid / 2 / (ms_die * 1e-3), 1)}}
+    if not args.no_cpu_baseline:
+        from oracle import embedding as oemb
+        n = min(t, 20000)
+        x = sets[0].dy[:n].double().cpu().numpy()
+        t0 = time.perf_counter()
+        oemb.embedding_bwd(x, ids_np[:n], vocab)
+        csec = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(n / csec, 1), "unit": "rows/s", "cores": 1, "kind": "oracle",
+                               "sample": "%d of %d rows, %.2f s" % (n, t, csec)}
     print(json.dumps(out))
 
 

@@ -258,6 +258,32 @@ int fmha_dropout_add_ln_bwd(const fmha_ln_params_t* p, const void* dy, const voi
                             float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes,
                             void* stream);
 
+/* ---- Backward of the embedding lookup ----------------------------------------
+ * Section IV-C-3 of the paper: the rows of the output gradient that share an index are
+ * accumulated into that row of the weight gradient, collisions resolved by atomic adds on
+ * packed pairs of 16-bit values (two adjacent columns per operation) with a fine work
+ * split.     dw[indices[t]][c] += dy[t][c]   for every row t < rows (and < *n_rows).
+ *   dy      : device, [rows, hidden] 16-bit (dtype), dense (read)
+ *   indices : device, int32 [rows]; entries outside [0, vocab) or equal to padding_idx
+ *             (pass -1 for none) contribute nothing
+ *   n_rows  : optional device int32 (rows actually present), NULL = rows
+ *   dw      : device, [vocab, hidden] 16-bit, 16-byte aligned; ACCUMULATED INTO, unless
+ *             FMHA_EMB_ZERO_FIRST asks for it to be cleared first (a fill kernel on `stream`)
+ *   hidden must be a multiple of 8.
+ * The additions happen in the 16-bit type, each rounded to nearest, in an order that is
+ * not fixed: a weight row that receives n rows carries an error of at most n half-ulps of
+ * the largest partial sum, and results can differ in the last bits from run to run; rows
+ * that receive one gradient row are exact.
+ * FMHA_EMB_PLAIN_SPLIT selects the token-major work split (wavefront w takes tokens w, w+W,
+ * ...) instead of the default, in which the tokens are divided among the chip's dies by
+ * index modulo 8 so that each weight row is only ever updated from one die's L2. */
+#define FMHA_EMB_ZERO_FIRST 1u
+#define FMHA_EMB_PLAIN_SPLIT 2u
+#define FMHA_EMB_NO_DIE_SPLIT 4u
+int fmha_embedding_bwd(const void* dy, const int32_t* indices, const int32_t* n_rows, int32_t rows,
+                       int32_t hidden, int32_t vocab, int32_t padding_idx, int32_t dtype,
+                       uint32_t flags, void* dw, void* stream);
+
 /* Number of 128-row tiles the schedule holds at most for this shape (host
  * arithmetic), and a device-to-host-free way for tests to locate the tile list
  * inside the workspace: the list starts at byte offset *list_offset and holds

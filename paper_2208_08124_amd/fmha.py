@@ -20,11 +20,15 @@ FMHA_F16, FMHA_BF16 = 0, 1
 FMHA_FLAG_REUSE_SCHEDULE = 1
 FMHA_FLAG_BWD_ONLY_DQ = 2
 FMHA_FLAG_BWD_ONLY_DKV = 4
+FMHA_EMB_ZERO_FIRST = 1
+FMHA_EMB_PLAIN_SPLIT = 2
+FMHA_EMB_NO_DIE_SPLIT = 4
 
 EXPORTS = ("fmha_varlen_workspace_size", "fmha_varlen_fwd", "fmha_varlen_bwd",
            "fmha_varlen_fwd_dropout", "fmha_varlen_bwd_dropout", "fmha_dropout_keep_mask",
            "fmha_unpad_indices_host", "fmha_unpad_indices", "fmha_gather_rows", "fmha_scatter_rows",
            "fmha_dropout_add_ln_fwd", "fmha_dropout_add_ln_bwd", "fmha_dropout_add_ln_bwd_workspace_size",
+           "fmha_embedding_bwd",
            "fmha_varlen_schedule_info", "fmha_last_error")
 
 
@@ -103,6 +107,8 @@ def lib():
         L.fmha_dropout_add_ln_bwd.restype = ctypes.c_int
         L.fmha_dropout_add_ln_bwd_workspace_size.argtypes = [i32, i32]
         L.fmha_dropout_add_ln_bwd_workspace_size.restype = ctypes.c_size_t
+        L.fmha_embedding_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_uint32, vp, vp]
+        L.fmha_embedding_bwd.restype = ctypes.c_int
         L.fmha_varlen_schedule_info.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_size_t)] * 2
         L.fmha_varlen_schedule_info.restype = ctypes.c_int32
         L.fmha_last_error.restype = ctypes.c_char_p
@@ -329,3 +335,15 @@ def fmha_dropout_add_ln_bwd(dy, z, mu, rstd, gamma, eps, dx, dresidual, dgamma, 
                                          None if dresidual is None else dresidual.data_ptr(),
                                          dgamma.data_ptr(), dbeta.data_ptr(), workspace.data_ptr(),
                                          workspace.numel() * workspace.element_size(), _stream()))
+
+
+def fmha_embedding_bwd(dy, indices, dw, *, padding_idx=-1, n_rows=None, zero_first=False, plain_split=False,
+                       no_die_split=False):
+    """dw[indices[t]] += dy[t] with packed 16-bit atomic adds; dy [T, N], indices int32 [T], dw [V, N]."""
+    assert dy.dim() == 2 and dw.dim() == 2 and dy.is_contiguous() and dw.is_contiguous() and dy.dtype == dw.dtype
+    assert indices.dtype == torch.int32 and indices.is_cuda and indices.numel() == dy.shape[0]
+    flags = ((FMHA_EMB_ZERO_FIRST if zero_first else 0) | (FMHA_EMB_PLAIN_SPLIT if plain_split else 0)
+             | (FMHA_EMB_NO_DIE_SPLIT if no_die_split else 0))
+    _check(lib().fmha_embedding_bwd(dy.data_ptr(), indices.data_ptr(), None if n_rows is None else n_rows.data_ptr(),
+                                    dy.shape[0], dy.shape[1], dw.shape[0], int(padding_idx), _dtype_code(dy), flags,
+                                    dw.data_ptr(), _stream()))

@@ -177,3 +177,14 @@ def useful_flops(lengths, heads: int, backward: bool) -> float:
     """4*sum(L^2)*H*d forward, plus 10*sum(L^2)*H*d backward (five contractions)."""
     s2 = float((np.asarray(lengths, dtype=np.float64) ** 2).sum())
     return (14.0 if backward else 4.0) * s2 * heads * HEAD_DIM
+
+
+def zipf_token_ids(n: int, vocab: int, seed: int, exponent: float = 1.0) -> np.ndarray:
+    """n token ids in [0, vocab) whose frequencies follow a Zipf law (rank r has weight
+    r**-exponent), the ranks assigned to ids by a seeded permutation: a stand-in for the
+    word-piece ids of the paper's Wikipedia batches (a few very frequent ids, a long tail)."""
+    rng = np.random.default_rng(seed)
+    w = np.arange(1, vocab + 1, dtype=np.float64) ** -exponent
+    cdf = np.cumsum(w / w.sum())
+    ranks = np.minimum(np.searchsorted(cdf, rng.random(n)), vocab - 1)
+    return rng.permutation(vocab)[ranks].astype(np.int32)

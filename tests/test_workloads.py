@@ -58,3 +58,14 @@ def test_padding_layout():
 def test_useful_flops():
     assert wl.useful_flops([3, 17, 64, 128], 2, False) == 4 * 20778 * 2 * 64
     assert wl.useful_flops([2], 1, True) == 14 * 4 * 64
+
+
+def test_zipf_token_ids_are_seeded_in_range_and_skewed():
+    a = wl.zipf_token_ids(20000, 30522, 7)
+    b = wl.zipf_token_ids(20000, 30522, 7)
+    assert np.array_equal(a, b) and a.dtype == np.int32 and a.min() >= 0 and a.max() < 30522
+    counts = np.sort(np.bincount(a, minlength=30522))[::-1]
+    # Zipf(1) over 30 522 ids: the most frequent id has about 1/H(V) = 9 % of the tokens,
+    # and a long tail of ids appears once or not at all
+    assert 0.06 < counts[0] / 20000 < 0.13 and counts[0] > 1.5 * counts[1] > 0
+    assert (counts <= 1).sum() > 20000
