@@ -92,10 +92,13 @@ int fmha_unpad_indices(const int32_t* input_mask, int32_t batch, int32_t seqlen,
 
 int fmha_gather_rows(const void* padded, int32_t padded_rows, const int32_t* nonzero_indices, const int32_t* n_rows,
                      int32_t packed_rows, int64_t row_bytes, void* packed, void* stream) {
+  if (packed_rows == 0) {  // nothing can be written: the buffers may be null
+    fmha_host::g_err[0] = 0;
+    return FMHA_OK;
+  }
   int rc = check_rows(padded, packed, nonzero_indices, n_rows, padded_rows, packed_rows, row_bytes);
   if (rc) return rc;
   fmha_host::g_err[0] = 0;
-  if (packed_rows == 0) return FMHA_OK;
   const int chunks = (int)(row_bytes / 16);
   fmha::gather_rows_kernel<<<copy_grid(packed_rows, chunks), 256, 0, static_cast<hipStream_t>(stream)>>>(
       static_cast<const uint4*>(padded), nonzero_indices, n_rows, padded_rows, chunks, packed_rows,
@@ -105,10 +108,13 @@ int fmha_gather_rows(const void* padded, int32_t padded_rows, const int32_t* non
 
 int fmha_scatter_rows(const void* packed, int32_t packed_rows, const int32_t* inverse, const int32_t* n_rows,
                       int32_t padded_rows, int64_t row_bytes, void* padded, void* stream) {
+  if (padded_rows == 0) {  // nothing to write: the buffers may be null
+    fmha_host::g_err[0] = 0;
+    return FMHA_OK;
+  }
   int rc = check_rows(packed, padded, inverse, n_rows, packed_rows, padded_rows, row_bytes);
   if (rc) return rc;
   fmha_host::g_err[0] = 0;
-  if (padded_rows == 0) return FMHA_OK;
   const int chunks = (int)(row_bytes / 16);
   fmha::scatter_rows_kernel<<<copy_grid(padded_rows, chunks), 256, 0, static_cast<hipStream_t>(stream)>>>(
       static_cast<const uint4*>(packed), inverse, n_rows, packed_rows, chunks, padded_rows,

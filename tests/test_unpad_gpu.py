@@ -93,6 +93,12 @@ def test_out_of_range_indices_give_zero_rows():
     assert torch.equal(back[0], x[1]) and torch.equal(back[3], x[0]) and (back[1] == 0).all() and (back[2] == 0).all()
 
 
+def test_empty_row_copies_are_accepted():
+    lib = fmha.lib()
+    assert lib.fmha_gather_rows(None, 0, None, None, 0, 0, None, None) == fmha.FMHA_OK
+    assert lib.fmha_scatter_rows(None, 0, None, None, 0, 0, None, None) == fmha.FMHA_OK
+
+
 def test_row_copy_argument_errors():
     x = torch.zeros((4, 8), dtype=torch.int16, device="cuda")
     idx = torch.zeros(4, dtype=torch.int32, device="cuda")
