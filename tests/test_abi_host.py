@@ -128,3 +128,73 @@ def test_backward_rejects_conflicting_pass_flags():
     a = [fk.p] * 10
     rc = fmha.lib().fmha_varlen_bwd(ctypes.byref(p), *a[:9], None)
     assert rc == fmha.FMHA_ERR_INVALID_ARG and "exclude" in fmha.last_error()
+
+
+def test_struct_layouts_against_the_c_compiler(tmp_path):
+    """sizeof / offsetof of every struct in the header as gcc sees them, against the ctypes mirrors."""
+    import subprocess
+    from paper_2208_08124_amd import fmha
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "%s"\n'
+                   'int main(void) {\n'
+                   '  printf("%%zu %%zu %%zu\\n", sizeof(fmha_varlen_params_t), offsetof(fmha_varlen_params_t, cu_seqlens), offsetof(fmha_varlen_params_t, workspace_bytes));\n'
+                   '  printf("%%zu %%zu\\n", sizeof(fmha_dropout_t), offsetof(fmha_dropout_t, seed));\n'
+                   '  printf("%%zu %%zu %%zu %%zu\\n", sizeof(fmha_ln_params_t), offsetof(fmha_ln_params_t, eps), offsetof(fmha_ln_params_t, n_rows), offsetof(fmha_ln_params_t, dropout));\n'
+                   '  return 0;\n}\n' % HEADER)
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Werror", "-o", str(exe), str(src)])
+    rows = [[int(x) for x in l.split()] for l in subprocess.check_output([str(exe)]).decode().splitlines()]
+    P, D, L = fmha.Params, fmha.Dropout, fmha.LnParams
+    assert rows[0] == [ctypes.sizeof(P), P.cu_seqlens.offset, P.workspace_bytes.offset]
+    assert rows[1] == [ctypes.sizeof(D), D.seed.offset]
+    assert rows[2] == [ctypes.sizeof(L), L.eps.offset, L.n_rows.offset, L.dropout.offset]
+
+
+def test_dropout_layernorm_embedding_reject_bad_arguments_without_a_device():
+    from paper_2208_08124_amd import fmha
+    lib, fk = fmha.lib(), Fake()
+    INV, UNS, WS = fmha.FMHA_ERR_INVALID_ARG, fmha.FMHA_ERR_UNSUPPORTED, fmha.FMHA_ERR_WORKSPACE
+    # dropout: null struct and p outside [0, 1)
+    p = fmha.Params()
+    p.batch, p.total_tokens, p.heads, p.head_dim = 1, 8, 1, 64
+    p.dtype, p.scale = fmha.FMHA_F16, 1.0
+    p.cu_seqlens, p.workspace, p.workspace_bytes = fk.p, fk.p, 1 << 20
+    six = [fk.p] * 5 + [None]
+    assert lib.fmha_varlen_fwd_dropout(ctypes.byref(p), None, *six) == INV and "dropout is null" in fmha.last_error()
+    for bad in (1.0, -0.5, float("nan")):
+        d = fmha.Dropout(bad, 1)
+        assert lib.fmha_varlen_fwd_dropout(ctypes.byref(p), ctypes.byref(d), *six) == INV
+        assert lib.fmha_varlen_bwd_dropout(ctypes.byref(p), ctypes.byref(d), *([fk.p] * 9), None) == INV
+    d = fmha.Dropout(0.1, 1)
+    assert lib.fmha_dropout_keep_mask(ctypes.byref(p), ctypes.byref(d), 2, 64, fk.p, None) == INV
+    assert lib.fmha_dropout_keep_mask(ctypes.byref(p), ctypes.byref(d), 0, 0, fk.p, None) == INV
+    # LayerNorm
+    lp = fmha.LnParams()
+    lp.rows, lp.hidden, lp.dtype, lp.eps = 4, 64, fmha.FMHA_F16, 1e-5
+    nine = [fk.p] * 8 + [None]
+    for field, val, code, frag in (("hidden", 40, INV, "multiple of 16"), ("hidden", 8192, UNS, "4096"),
+                                   ("dtype", 9, UNS, "dtype"), ("rows", -1, INV, "rows"),
+                                   ("eps", -1.0, INV, "eps")):
+        q = fmha.LnParams.from_buffer_copy(lp)
+        setattr(q, field, val)
+        assert lib.fmha_dropout_add_ln_fwd(ctypes.byref(q), *nine) == code, field
+        assert frag in fmha.last_error(), (field, fmha.last_error())
+    assert lib.fmha_dropout_add_ln_fwd(None, *nine) == INV
+    assert lib.fmha_dropout_add_ln_fwd(ctypes.byref(lp), None, *nine[1:]) == INV and "x is null" in fmha.last_error()
+    assert lib.fmha_dropout_add_ln_bwd(ctypes.byref(lp), *([fk.p] * 9), None, 0, None) == WS
+    assert fmha.fmha_dropout_add_ln_bwd_workspace_size(15769, 1024) == 256 * 2 * 1024 * 4
+    assert fmha.fmha_dropout_add_ln_bwd_workspace_size(10, 1024) == 1 * 2 * 1024 * 4
+    # embedding
+    e = lib.fmha_embedding_bwd
+    assert e(fk.p, fk.p, None, 4, 64, 10, -1, 5, 0, fk.p, None) == UNS
+    assert e(fk.p, fk.p, None, 4, 60, 10, -1, 0, 0, fk.p, None) == INV and "multiple of 8" in fmha.last_error()
+    assert e(fk.p, fk.p, None, 4, 64, 0, -1, 0, 0, fk.p, None) == INV
+    assert e(None, fk.p, None, 4, 64, 10, -1, 0, 0, fk.p, None) == INV
+    assert e(fk.p, fk.p, None, 4, 64, 10, -1, 0, 0, None, None) == INV
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
