@@ -61,6 +61,25 @@ static __device__ __forceinline__ void load16(const uint16_t* p, float (&f)[16])
   }
 }
 
+// the same in two steps, so that the loads of the next row can be in flight while the
+// current one is worked on
+struct Raw16 {
+  u32x4 a, b;
+};
+static __device__ __forceinline__ Raw16 load16_raw(const uint16_t* p) {
+  return Raw16{*reinterpret_cast<const u32x4*>(p), *reinterpret_cast<const u32x4*>(p + 8)};
+}
+template <typename T>
+static __device__ __forceinline__ void unpack16(const Raw16& w, float (&f)[16]) {
+#pragma unroll
+  for (int e = 0; e < 4; e++) {
+    f[2 * e] = Cvt<T>::lo(w.a[e]);
+    f[2 * e + 1] = Cvt<T>::hi(w.a[e]);
+    f[8 + 2 * e] = Cvt<T>::lo(w.b[e]);
+    f[8 + 2 * e + 1] = Cvt<T>::hi(w.b[e]);
+  }
+}
+
 template <typename T>
 static __device__ __forceinline__ void store16(uint16_t* p, const float (&f)[16]) {
   u32x4 a, b;
@@ -112,17 +131,39 @@ __global__ __launch_bounds__(kLnFwdThreads) void ln_fwd_kernel(const LnArgs a, c
   const int n = a.hidden, rows = ln_rows(a);
   const float inv_n = 1.f / (float)n;
   const int per_grid = gridDim.x * (kLnFwdThreads / 64);
-  for (int row = blockIdx.x * (kLnFwdThreads / 64) + wave; row < rows; row += per_grid) {
+  // the next row's x and residual are requested before the current row is worked on
+  Raw16 nx[CPL], nr[CPL];
+  auto fetch = [&](int row) {
+    const int64_t base = (int64_t)row * n;
+#pragma unroll
+    for (int i = 0; i < CPL; i++) {
+      const int ci = lane + 64 * i;
+      if (16 * ci < n) {
+        nx[i] = load16_raw(x + base + 16 * ci);
+        nr[i] = load16_raw(r + base + 16 * ci);
+      }
+    }
+  };
+  const int first = blockIdx.x * (kLnFwdThreads / 64) + wave;
+  if (first < rows) fetch(first);
+  for (int row = first; row < rows; row += per_grid) {
     const int64_t base = (int64_t)row * n;
     float zf[CPL][16];
     float sum = 0.f;
+    Raw16 cx[CPL], cr[CPL];
+#pragma unroll
+    for (int i = 0; i < CPL; i++) {
+      cx[i] = nx[i];
+      cr[i] = nr[i];
+    }
+    if (row + per_grid < rows) fetch(row + per_grid);
 #pragma unroll
     for (int i = 0; i < CPL; i++) {
       const int ci = lane + 64 * i;
       if (16 * ci < n) {
         float xf[16], rf[16];
-        load16<T>(x + base + 16 * ci, xf);
-        load16<T>(r + base + 16 * ci, rf);
+        unpack16<T>(cx[i], xf);
+        unpack16<T>(cr[i], rf);
         if (DROP) {
           float m[16];
           keep16(m, ci, row, a.drop);
