@@ -123,7 +123,7 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const Bw
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
-  TileItem ti_next = load_tile(a.pb, (blockIdx.x < n_items ? blockIdx.x : 0) / heads);
+  TileItem ti_next = load_tile(a.pb, ((int)blockIdx.x < n_items ? (int)blockIdx.x : 0) / heads);
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
     const TileItem ti = ti_next;
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
-  TileItem ti_next = load_tile(a.pb, (blockIdx.x < n_items ? blockIdx.x : 0) / heads);
+  TileItem ti_next = load_tile(a.pb, ((int)blockIdx.x < n_items ? (int)blockIdx.x : 0) / heads);
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
     const int head = item % heads;
     const TileItem ti = ti_next;
