@@ -111,8 +111,8 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const Bw
   const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
   constexpr uint32_t kTileBytes = kTileElems * 2;
   // this lane's piece within a 64-row block (rows dl.row and dl.row + 32), in elements
-  const uint32_t k_lane = dl.row * (uint32_t)a.k_stride + dl.chunk * 8;
-  const uint32_t v_lane = dl.row * (uint32_t)a.v_stride + dl.chunk * 8;
+  const uint32_t k_lane = (dl.row * (uint32_t)a.k_stride + dl.chunk * 8) * 2u;  // bytes
+  const uint32_t v_lane = (dl.row * (uint32_t)a.v_stride + dl.chunk * 8) * 2u;
 
   // one entry behind each statistics array stands for "row past the end" in pass 2:
   // LSE = +inf makes its probabilities vanish
@@ -139,19 +139,15 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const Bw
     const uint16_t* vbase = a.v + (int64_t)r0 * a.v_stride + head * kHeadDim;
     const int n = (nk + kBlockKeys - 1) / kBlockKeys;
 
-    // (the empty asm keeps the 64-bit sums from being formed ahead of the item loop
-    // and held in registers through it)
+    // (the empty asm keeps the lane offsets from being combined with anything ahead of the
+    // item loop and held in registers through it)
     uint32_t kl = k_lane, vl = v_lane;
     asm volatile("" : "+v"(kl), "+v"(vl));
-    const uint16_t* kpa = kbase + kl;
-    const uint16_t* vpa = vbase + vl;
     auto start_block = [&](int kt, int stage) {  // 4 pieces per thread
       const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
       if ((kt + 1) * kBlockKeys <= nk) {
-        const uint16_t* pk = kpa + (int64_t)kt * kBlockKeys * a.k_stride;
-        const uint16_t* pv = vpa + (int64_t)kt * kBlockKeys * a.v_stride;
-        dma_tile_full(pk, pk + 32 * a.k_stride, wave, st_addr);
-        dma_tile_full(pv, pv + 32 * a.v_stride, wave, st_addr + kTileBytes);
+        dma_tile_full(kbase + (int64_t)kt * kBlockKeys * a.k_stride, kl, a.k_stride, wave, st_addr);
+        dma_tile_full(vbase + (int64_t)kt * kBlockKeys * a.v_stride, vl, a.v_stride, wave, st_addr + kTileBytes);
       } else {
         dma_tile(kbase, a.k_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr);
         dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
@@ -163,14 +159,16 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const Bw
     // LSE of this lane's query as ordinary loads.
     {
       const uint32_t own_addr = ring_addr + (kBwdStages - 1) * (2 * kTileBytes) + 1024u * wave;
-      const uint16_t* qbase = a.q + (int64_t)r0 * a.q_stride + head * kHeadDim;
+      // rows relative to the wavefront's first row, clamped into the sequence
+      const int w0 = min(ti.row0 + 32 * wave, len - 1);
+      const uint16_t* qrows = a.q + uniform_i64((int64_t)(r0 + w0) * a.q_stride + head * kHeadDim);
       const int le = lane_id();
+      const int room = len - 1 - w0;
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const int r = 8 * i + (le >> 3);  // row within the wavefront's 32
-        const int qr = min(ti.row0 + 32 * wave + r, len - 1);
-        dma16(qbase + (int64_t)qr * a.q_stride + ((le & 7) ^ swz(r)) * 8,
-              __builtin_amdgcn_readfirstlane(own_addr + own_piece(i)));
+        const uint32_t off = ((uint32_t)min(r, room) * (uint32_t)a.q_stride + ((le & 7) ^ swz(r)) * 8) * 2u;
+        dma16s(qrows, off, __builtin_amdgcn_readfirstlane(own_addr + own_piece(i)));
       }
     }
     if (n > 0) start_block(0, 0);
@@ -252,8 +250,8 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const Bw
     // dQ leaves as whole rows, turned around in the wavefront's private rows of
     // the last ring stage (see store_rows).
     if (wave_on)
-      store_rows<T>(dq, a.pb.scale, &ring[kBwdStages - 1][0][0], wave,
-                    a.dq + (int64_t)(r0 + ti.row0 + 32 * wave) * a.dq_stride + head * kHeadDim, a.dq_stride,
+      store_rows<T>(dq, a.pb.scale, &ring[kBwdStages - 1][0][0], wave, a.dq,
+                    (int64_t)(r0 + ti.row0 + 32 * wave) * a.dq_stride + head * kHeadDim, a.dq_stride,
                     len - (ti.row0 + 32 * wave));
   }
 }
@@ -365,8 +363,8 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
   const uint32_t ring_addr = lds_addr(&ring[0]);
   constexpr uint32_t kStageBytes = sizeof(DkvStage), kTileBytes = kTileElems * 2;
   // this lane's piece within a 64-row block (rows dl.row and dl.row + 32), in elements
-  const uint32_t q_lane = dl.row * (uint32_t)a.q_stride + dl.chunk * 8;
-  const uint32_t g_lane = dl.row * (uint32_t)a.do_stride + dl.chunk * 8;
+  const uint32_t q_lane = (dl.row * (uint32_t)a.q_stride + dl.chunk * 8) * 2u;  // bytes
+  const uint32_t g_lane = (dl.row * (uint32_t)a.do_stride + dl.chunk * 8) * 2u;
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
@@ -393,19 +391,15 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
     const float* stat_pad = stat_arr + (int64_t)heads * a.pb.total_tokens;
     const int n = tile_on ? (len + kBlockKeys - 1) / kBlockKeys : 0;  // query blocks
 
-    // (the empty asm keeps the 64-bit sums from being formed ahead of the item loop
-    // and held in registers through it)
+    // (the empty asm keeps the lane offsets from being combined with anything ahead of the
+    // item loop and held in registers through it)
     uint32_t ql = q_lane, gl = g_lane;
     asm volatile("" : "+v"(ql), "+v"(gl));
-    const uint16_t* qpa = qbase + ql;
-    const uint16_t* gpa = gbase + gl;
     auto start_block = [&](int qt, int stage) {  // 5 pieces per thread
       const uint32_t st_addr = ring_addr + stage * kStageBytes;
       if ((qt + 1) * kBlockKeys <= len) {
-        const uint16_t* pq = qpa + (int64_t)qt * kBlockKeys * a.q_stride;
-        const uint16_t* pg = gpa + (int64_t)qt * kBlockKeys * a.do_stride;
-        dma_tile_full(pq, pq + 32 * a.q_stride, wave, st_addr);
-        dma_tile_full(pg, pg + 32 * a.do_stride, wave, st_addr + kTileBytes);
+        dma_tile_full(qbase + (int64_t)qt * kBlockKeys * a.q_stride, ql, a.q_stride, wave, st_addr);
+        dma_tile_full(gbase + (int64_t)qt * kBlockKeys * a.do_stride, gl, a.do_stride, wave, st_addr + kTileBytes);
       } else {
         dma_tile(qbase, a.q_stride, qt * kBlockKeys, len - 1, dl, wave, st_addr);
         dma_tile(gbase, a.do_stride, qt * kBlockKeys, len - 1, dl, wave, st_addr + kTileBytes);
@@ -475,9 +469,9 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
       }
       const int64_t tok = r0 + ti.row0 + 32 * wave;
       const int n_rows = len - (ti.row0 + 32 * wave);
-      store_rows<T>(dk, a.pb.scale, ring[kBwdStages - 1].q, wave, a.dk + tok * a.dk_stride + head * kHeadDim,
+      store_rows<T>(dk, a.pb.scale, ring[kBwdStages - 1].q, wave, a.dk, tok * a.dk_stride + head * kHeadDim,
                     a.dk_stride, n_rows);
-      store_rows<T>(dv, DROP ? a.drop.rp : 1.f, ring[kBwdStages - 2].q, wave, a.dv + tok * a.dv_stride + head * kHeadDim,
+      store_rows<T>(dv, DROP ? a.drop.rp : 1.f, ring[kBwdStages - 2].q, wave, a.dv, tok * a.dv_stride + head * kHeadDim,
                     a.dv_stride, n_rows);
     }
   }

@@ -174,8 +174,8 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void fmha_fwd_kernel(const 
   const uint32_t ring_addr = lds_addr(&ring[0][0][0]);
   constexpr uint32_t kTileBytes = kTileElems * 2;
   // this lane's piece within a 64-row block (rows dl.row and dl.row + 32), in elements
-  const uint32_t k_lane = dl.row * (uint32_t)a.k_stride + dl.chunk * 8;
-  const uint32_t v_lane = dl.row * (uint32_t)a.v_stride + dl.chunk * 8;
+  const uint32_t k_lane = (dl.row * (uint32_t)a.k_stride + dl.chunk * 8) * 2u;  // bytes
+  const uint32_t v_lane = (dl.row * (uint32_t)a.v_stride + dl.chunk * 8) * 2u;
 
   // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
   // next item is fetched while the current one is computed.
@@ -194,19 +194,15 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void fmha_fwd_kernel(const 
     const int n = (nk + kBlockKeys - 1) / kBlockKeys;  // blocks of 64 keys
 
     // Start moving key block kt into ring stage `stage`: 4 pieces per thread.
-    // (the empty asm keeps the 64-bit sums from being formed ahead of the item loop
-    // and held in registers through it)
+    // (the empty asm keeps the lane offsets from being combined with anything ahead of the
+    // item loop and held in registers through it)
     uint32_t kl = k_lane, vl = v_lane;
     asm volatile("" : "+v"(kl), "+v"(vl));
-    const uint16_t* kpa = kbase + kl;
-    const uint16_t* vpa = vbase + vl;
     auto start_block = [&](int kt, int stage) {
       const uint32_t st_addr = ring_addr + stage * (2 * kTileBytes);
       if ((kt + 1) * kBlockKeys <= nk) {
-        const uint16_t* pk = kpa + (int64_t)kt * kBlockKeys * a.k_stride;
-        const uint16_t* pv = vpa + (int64_t)kt * kBlockKeys * a.v_stride;
-        dma_tile_full(pk, pk + 32 * a.k_stride, wave, st_addr);
-        dma_tile_full(pv, pv + 32 * a.v_stride, wave, st_addr + kTileBytes);
+        dma_tile_full(kbase + (int64_t)kt * kBlockKeys * a.k_stride, kl, a.k_stride, wave, st_addr);
+        dma_tile_full(vbase + (int64_t)kt * kBlockKeys * a.v_stride, vl, a.v_stride, wave, st_addr + kTileBytes);
       } else {
         dma_tile(kbase, a.k_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr);
         dma_tile(vbase, a.v_stride, kt * kBlockKeys, nk - 1, dl, wave, st_addr + kTileBytes);
@@ -218,14 +214,17 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void fmha_fwd_kernel(const 
     // ahead of the first two key blocks; they are awaited together with block 0.
     const uint32_t own_addr = ring_addr + (kFwdStages - 1) * (2 * kTileBytes) + 1024u * wave;
     {
-      const uint16_t* qbase = a.q + (int64_t)r0 * a.q_stride + head * kHeadDim;
+      // rows relative to the wavefront's first row (clamped into the sequence, so that the
+      // offsets of a wavefront that lies entirely past the end stay non-negative)
+      const int w0 = min(ti.row0 + 32 * wave, len - 1);
+      const uint16_t* qrows = a.q + uniform_i64((int64_t)(r0 + w0) * a.q_stride + head * kHeadDim);
       const int le = lane_id();
+      const int room = len - 1 - w0;
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const int r = 8 * i + (le >> 3);  // row within the wavefront's 32
-        const int qr = min(ti.row0 + 32 * wave + r, len - 1);
-        dma16(qbase + (int64_t)qr * a.q_stride + ((le & 7) ^ swz(r)) * 8,
-              __builtin_amdgcn_readfirstlane(own_addr + own_piece(i)));
+        const uint32_t off = ((uint32_t)min(r, room) * (uint32_t)a.q_stride + ((le & 7) ^ swz(r)) * 8) * 2u;
+        dma16s(qrows, off, __builtin_amdgcn_readfirstlane(own_addr + own_piece(i)));
       }
     }
     if (n > 0) start_block(0, 0);
@@ -292,11 +291,12 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void fmha_fwd_kernel(const 
       const float inv = l_tot > 0.f ? (DROP ? a.drop.rp : 1.f) / l_tot : 0.f;
       const int le = lane_id();
       const int qrow = ti.row0 + 32 * wave + (le & 31);  // this lane's query, within the sequence
-      if (qrow < len && le < 32)
-        a.lse[(int64_t)head * a.pb.total_tokens + r0 + qrow] =
-            l_tot > 0.f ? (acc.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-      store_rows<T>(acc.o, inv, &ring[kFwdStages - 1][0][0], wave,
-                    a.o + (int64_t)(r0 + ti.row0 + 32 * wave) * a.o_stride + head * kHeadDim, a.o_stride,
+      if (qrow < len && le < 32) {
+        float* lrow = a.lse + uniform_i64((int64_t)head * a.pb.total_tokens + r0 + ti.row0 + 32 * wave);
+        lrow[le & 31] = l_tot > 0.f ? (acc.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+      }
+      store_rows<T>(acc.o, inv, &ring[kFwdStages - 1][0][0], wave, a.o,
+                    (int64_t)(r0 + ti.row0 + 32 * wave) * a.o_stride + head * kHeadDim, a.o_stride,
                     len - (ti.row0 + 32 * wave));
     }
   }

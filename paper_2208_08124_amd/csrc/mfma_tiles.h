@@ -189,6 +189,25 @@ static __device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_byte_
                : "memory");
 }
 
+// The same with the address split into a wave-uniform base (scalar registers) and a
+// 32-bit byte offset per lane: no 64-bit vector arithmetic per transfer.
+static __device__ __forceinline__ void dma16s(const void* sbase, uint32_t voff, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(lds_byte_addr), "v"(voff), "s"(sbase)
+               : "memory");
+}
+
+// An offset the compiler may keep in scalar registers: the value is the same in every lane
+// (it depends on the wavefront index at most), which the compiler cannot always see.  Added
+// to a kernel-argument pointer it gives a wave-uniform base that still carries the pointer's
+// address space (a pointer rebuilt from integers would be accessed with flat instructions).
+static __device__ __forceinline__ int64_t uniform_i64(int64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 template <int N>
 static __device__ __forceinline__ void wait_vmem() {
   asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
@@ -205,24 +224,29 @@ struct DmaLane {
   }
 };
 
-// Start moving 64 full rows: pa / pb point at this lane's chunk in its two rows.
-static __device__ __forceinline__ void dma_tile_full(const uint16_t* pa, const uint16_t* pb,
+// Start moving 64 full rows that begin at `rows` (wave-uniform: first row, this head);
+// lane_bytes = byte offset of this lane's chunk within its first row (DmaLane: row * stride +
+// chunk * 8 elements), stride in elements.
+static __device__ __forceinline__ void dma_tile_full(const uint16_t* rows, uint32_t lane_bytes, int64_t stride,
                                                      int wave, uint32_t tile_addr) {
   const uint32_t m0 = __builtin_amdgcn_readfirstlane(tile_addr + 1024u * wave);
-  dma16(pa, m0);
-  dma16(pb, m0 + 4096u);
+  dma16s(rows, lane_bytes, m0);
+  dma16s(rows + 32 * stride, lane_bytes, m0 + 4096u);
 }
 
 // Start moving rows [row0, row0 + 64) of a packed tensor (rows clamped to
 // last_row, so the tail of a short sequence repeats its last valid row instead
 // of reading past it) into the tile at LDS byte address `tile_addr`.
+// (row0 <= last_row; the lane offsets are relative to row0, so they fit 32 bits)
 static __device__ __forceinline__ void dma_tile(const uint16_t* base, int64_t stride, int row0,
                                                 int last_row, const DmaLane& dl, int wave,
                                                 uint32_t tile_addr) {
-  const int ra = min(row0 + dl.row, last_row), rb = min(row0 + dl.row + 32, last_row);
+  const int ra = min(dl.row, last_row - row0), rb = min(dl.row + 32, last_row - row0);
   const uint32_t m0 = __builtin_amdgcn_readfirstlane(tile_addr + 1024u * wave);
-  dma16(base + ra * stride + dl.chunk * 8, m0);
-  dma16(base + rb * stride + dl.chunk * 8, m0 + 4096u);
+  const uint16_t* rows = base + uniform_i64(row0 * stride);
+  const uint32_t st = (uint32_t)stride;
+  dma16s(rows, (ra * st + dl.chunk * 8) * 2u, m0);
+  dma16s(rows, (rb * st + dl.chunk * 8) * 2u, m0 + 4096u);
 }
 
 // ---------------------------------------------------------------------------
@@ -269,14 +293,14 @@ __device__ __forceinline__ int lane_id() {
 
 // A wavefront's 32 x 64 result tile, held transposed in MFMA layout (x[cb][r] =
 // channel 32cb + 8(r/4) + 4g + r%4 of row ln), scaled, rounded to T and written to
-// global memory as whole 128-byte rows: the tile is turned around in the
+// global memory as whole 128-byte rows (row 0 of the tile is at out_tensor + out_offset, a
+// wave-uniform position): the tile is turned around in the
 // wavefront's private pieces of `stage` (piece r/8 holds rows 8(r/8)..+7, 16-byte
 // chunk c of row r at position c ^ swz(r)), so that each store instruction covers
-// 8 complete rows instead of 16 bytes in each of 32.  `out` points at row 0 of the
-// tile, rows >= n_rows are not stored.  All 64 lanes must be active.
+// 8 complete rows instead of 16 bytes in each of 32.  Rows >= n_rows are not stored.  All 64 lanes must be active.
 template <typename T>
 __device__ __forceinline__ void store_rows(const f32x16 (&x)[2], float scale, uint16_t* stage, int wave,
-                                           uint16_t* out, int64_t out_stride, int n_rows,
+                                           uint16_t* out_tensor, int64_t out_offset, int64_t out_stride, int n_rows,
                                            int second_tile = 8192) {
   // lane-derived addresses are computed here rather than kept in registers by the caller
   const int lane = lane_id();
@@ -294,12 +318,15 @@ __device__ __forceinline__ void store_rows(const f32x16 (&x)[2], float scale, ui
     }
   __builtin_amdgcn_wave_barrier();  // same wavefront: its LDS operations execute in order
   const int chunk = lane & 7;
+  // `out` is the same in all lanes: base in scalar registers, 32-bit byte offsets per lane
+  char* ob = reinterpret_cast<char*>(out_tensor + uniform_i64(out_offset));
+  const uint32_t row_bytes = (uint32_t)out_stride * 2u;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int row = 8 * i + (lane >> 3);
     const u32x4 w = *reinterpret_cast<const u32x4*>(so + own_piece(i, second_tile) / 2 + (lane >> 3) * 64 +
                                                     ((chunk ^ swz(row)) << 3));
-    if (row < n_rows) *reinterpret_cast<u32x4*>(out + (int64_t)row * out_stride + 8 * chunk) = w;
+    if (row < n_rows) *reinterpret_cast<u32x4*>(ob + ((uint32_t)row * row_bytes + 16u * chunk)) = w;
   }
 }
 
