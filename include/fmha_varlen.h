@@ -24,8 +24,8 @@
  *   - Tensors are token-major: element (t, h, c) of Q is at
  *     q[t * q_stride + h * 64 + c], 0 <= t < total_tokens, 0 <= h < heads,
  *     0 <= c < 64, 16-bit elements (IEEE half or bfloat16).  A stride of 0
- *     means heads * 64 (dense).  Strides are in elements and must be
- *     multiples of 8; base pointers must be 16-byte aligned.
+ *     means heads * 64 (dense).  Strides are in elements, must be
+ *     multiples of 8 and at most 2^24; base pointers must be 16-byte aligned.
  *   - Sequence i owns rows cu_seqlens[i] .. cu_seqlens[i+1]-1.  Rows of
  *     different sequences never interact.  Empty sequences are allowed.
  *   - Inputs are read-only.  Outputs are fully overwritten for all rows.

@@ -75,6 +75,8 @@ int check_stride(const char* name, int64_t s, int64_t dense, int64_t* out) {
   if (s == 0) s = dense;
   if (s < dense || (s & 7)) return fail(FMHA_ERR_INVALID_ARG, "%s_stride=%lld must be 0 or a multiple of 8 that is >= heads*64=%lld",
                                         name, (long long)s, (long long)dense);
+  // the kernels address the 64 rows of a block with 32-bit byte offsets from a 64-bit base
+  if (s > ((int64_t)1 << 24)) return fail(FMHA_ERR_INVALID_ARG, "%s_stride=%lld exceeds 2^24 elements", name, (long long)s);
   *out = s;
   return FMHA_OK;
 }

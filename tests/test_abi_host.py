@@ -102,6 +102,7 @@ def test_forward_rejects_bad_arguments_without_a_device():
         (dict(o=Fake().p + 2), INV, "aligned"),
         (dict(q_stride=64), INV, "q_stride"),        # smaller than heads*64
         (dict(v_stride=132), INV, "v_stride"),       # not a multiple of 8
+        (dict(k_stride=(1 << 24) + 8), INV, "2^24"),
         (dict(workspace=0), WS, "workspace"),
         (dict(workspace_bytes=64), WS, "workspace"),
         (dict(cu_host=[1, 8, 16]), INV, "expected 0"),
