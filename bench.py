@@ -26,6 +26,12 @@ PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # MI355X dense MFMA, published
 HBM_GBS = 8000.0
 # HBM bytes per launch on workload 3 from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs, scaled by
 # a plain-copy reference (factors 2.0 and 1.0); see profiles/fmha_kernels_bert_large_fwd_bwd.md
+# the same for the other --op modes on workload 3's shapes (profiles/*_kernels*.md)
+MEASURED_TRAFFIC_OTHER_CFG3 = {"gather_rows": 32.9e6 + 32.3e6, "scatter_rows": 33.3e6 + 58.7e6,
+                               "unpad_indices": 0.27e6 + 0.18e6,
+                               "ln_fwd_kernel": 64.7e6 + 65.5e6,
+                               "ln_bwd (rows + columns)": 65.3e6 + 67.0e6 + 2.1e6,
+                               "embedding_bwd_window_kernel": 32.7e6 + 26.3e6}
 MEASURED_TRAFFIC_CFG3 = {"fmha_fwd_kernel": 97.3e6 + 33.3e6, "bwd_dq_kernel": 163.4e6 + 34.4e6,
                          "bwd_dkv_kernel": 132.3e6 + 64.6e6}
 
@@ -353,7 +359,8 @@ def bench_unpad(args, torch, fmha, wl):
                       "max_seqlen": s, "row_bytes": row_bytes, "valid_rows": t, "padded_rows": rows,
                       "buffer_sets": n_sets},
            "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(gbs[dom], 1), "peak": HBM_GBS,
-                        "unit": "GB/s", "frac": round(gbs[dom] / HBM_GBS, 4), "traffic": None,
+                        "unit": "GB/s", "frac": round(gbs[dom] / HBM_GBS, 4),
+                        "traffic": MEASURED_TRAFFIC_OTHER_CFG3.get(dom) if args.config == 3 else None,
                         "avg_launch_ms": round(k_ms[dom], 5),
                         "kernels_ms": {k: round(v, 5) for k, v in k_ms.items()},
                         "kernels_GBs": {k: round(v, 1) for k, v in gbs.items()},
@@ -433,7 +440,8 @@ def bench_layernorm(args, torch, fmha, wl):
            "config": {"workload": w.name + "_hidden_rows", "baseline_config": args.config, "rows": t,
                       "hidden": hid, "storage": w.dtype, "dropout_p": p, "buffer_sets": n_sets},
            "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(gbs[dom], 1), "peak": HBM_GBS,
-                        "unit": "GB/s", "frac": round(gbs[dom] / HBM_GBS, 4), "traffic": None,
+                        "unit": "GB/s", "frac": round(gbs[dom] / HBM_GBS, 4),
+                        "traffic": MEASURED_TRAFFIC_OTHER_CFG3.get(dom) if (args.config == 3 and args.dropout == 0) else None,
                         "avg_launch_ms": round(k_ms[dom], 5),
                         "kernels_ms": {k: round(v, 5) for k, v in k_ms.items()},
                         "kernels_GBs": {k: round(v, 1) for k, v in gbs.items()},
@@ -505,7 +513,8 @@ def bench_embedding(args, torch, fmha, wl):
                       "most_frequent_id_count": top, "buffer_sets": n_sets},
            "roofline": {"bound": "hbm", "kernel": "embedding_bwd_window_kernel",
                         "achieved": round(alg / (ms_die * 1e-3) / 1e9, 1), "peak": HBM_GBS, "unit": "GB/s",
-                        "frac": round(alg / (ms_die * 1e-3) / 1e9 / HBM_GBS, 4), "traffic": None,
+                        "frac": round(alg / (ms_die * 1e-3) / 1e9 / HBM_GBS, 4),
+                        "traffic": MEASURED_TRAFFIC_OTHER_CFG3["embedding_bwd_window_kernel"] if args.config == 3 else None,
                         "avg_launch_ms": round(ms_die, 5), "algorithmic_bytes": alg,
                         "kernels_ms": {"embedding_bwd_window_kernel (default: duplicates merged, split by die)": round(ms_die, 5),
                                        "embedding_bwd_window_kernel (duplicates merged, no die split)": round(ms_nodie, 5),
