@@ -81,27 +81,47 @@ __global__ __launch_bounds__(kEmbThreads) void embedding_bwd_kernel(const EmbArg
   }
 }
 
-// The rows of `members` (a set of lanes of the current 64-token window, all with index v)
-// summed in fp32 and added onto weight row v with one set of atomics.
-template <bool BF16>
-static __device__ __forceinline__ void add_rows_grouped(const EmbArgs& a, int t0, uint64_t members, int v, int lane,
-                                                        int c_begin, int c_end) {
+// The rows named by `members` (NW sets of lanes, one per 64-token sub-window starting at
+// t0 + 64k; all these tokens have index v) summed in fp32 and added onto weight row v with one
+// set of atomics.
+template <bool BF16, int NW>
+static __device__ __forceinline__ void add_rows_grouped(const EmbArgs& a, int t0, const uint64_t (&members)[NW], int v,
+                                                        int lane, int c_begin, int c_end) {
   uint32_t* dst = a.dw + (int64_t)v * a.pairs;
   for (int c0 = c_begin; c0 < c_end; c0 += 256) {
     float lo[4] = {0.f, 0.f, 0.f, 0.f}, hi[4] = {0.f, 0.f, 0.f, 0.f};
-    for (uint64_t m = members; m; m &= m - 1) {  // uniform
-      const uint32_t* src = a.dy + (int64_t)(t0 + __builtin_ctzll(m)) * a.pairs;
 #pragma unroll
-      for (int u = 0; u < 4; u++) {
-        const int c = c0 + 64 * u + lane;
-        const uint32_t x = c < c_end ? src[c] : 0u;
-        if (BF16) {
-          lo[u] += __builtin_bit_cast(float, x << 16);
-          hi[u] += __builtin_bit_cast(float, x & 0xffff0000u);
-        } else {
-          lo[u] += (float)__builtin_bit_cast(_Float16, (uint16_t)(x & 0xffffu));
-          hi[u] += (float)__builtin_bit_cast(_Float16, (uint16_t)(x >> 16));
+    for (int k = 0; k < NW; k++) {
+      uint64_t m = members[k];
+      while (m) {  // uniform; up to four member rows per trip, all their loads in flight together
+        int row[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          row[j] = m ? t0 + 64 * k + __builtin_ctzll(m) : -1;
+          m &= m - 1;  // 0 stays 0
         }
+        uint32_t x[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const uint32_t* src = a.dy + (int64_t)(row[j] < 0 ? row[0] : row[j]) * a.pairs;
+#pragma unroll
+          for (int u = 0; u < 4; u++) {
+            const int c = c0 + 64 * u + lane;
+            x[j][u] = (row[j] >= 0 && c < c_end) ? src[c] : 0u;
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+          for (int u = 0; u < 4; u++) {
+            if (BF16) {
+              lo[u] += __builtin_bit_cast(float, x[j][u] << 16);
+              hi[u] += __builtin_bit_cast(float, x[j][u] & 0xffff0000u);
+            } else {
+              lo[u] += (float)__builtin_bit_cast(_Float16, (uint16_t)(x[j][u] & 0xffffu));
+              hi[u] += (float)__builtin_bit_cast(_Float16, (uint16_t)(x[j][u] >> 16));
+            }
+          }
       }
     }
 #pragma unroll
@@ -119,13 +139,14 @@ static __device__ __forceinline__ void add_rows_grouped(const EmbArgs& a, int t0
   }
 }
 
-// Default variant.  A workgroup looks at 64 consecutive tokens at a time, one index per lane
-// (each of its 4 wavefronts reads the same 64 indices and takes a quarter of the columns).
+// Default variant.  A workgroup looks at 64 * NW consecutive tokens at a time, NW indices per
+// lane (each of its 4 wavefronts reads the same indices and takes a quarter of the columns).
 // Tokens of the window that share an index are first summed in registers (fp32) and reach
 // memory as ONE row of atomics: with word-piece ids a handful of indices take a large share of
-// the tokens, and every atomic on the same address waits for the one before it.
+// the tokens, and every atomic on the same address waits for the one before it.  NW = 1 for
+// small batches (more workgroups), NW = 4 for large ones (more merging).
 // DIE (gridDim.x a multiple of 8): workgroup b only takes the indices congruent to b modulo 8.
-template <bool BF16, bool DIE>
+template <bool BF16, bool DIE, int NW>
 __global__ __launch_bounds__(kEmbThreads) void embedding_bwd_window_kernel(const EmbArgs a) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int rows = emb_rows(a);
@@ -135,20 +156,37 @@ __global__ __launch_bounds__(kEmbThreads) void embedding_bwd_window_kernel(const
   const int quarter = ((a.pairs + 4 * 64 - 1) / (4 * 64)) * 64;  // columns per wavefront, whole 256-byte runs
   const int c_begin = min(wave * quarter, a.pairs), c_end = min(c_begin + quarter, a.pairs);
   if (c_begin >= c_end) return;  // uniform over the wavefront; no barriers below
-  for (int t0 = me * 64; t0 < rows; t0 += per * 64) {
-    const int t = t0 + lane;
-    const int v = t < rows ? a.indices[t] : -1;
-    const bool mine = v >= 0 && v < a.vocab && v != a.padding_idx && (!DIE || (v & 7) == die);
-    uint64_t todo = __ballot(mine);
-    while (todo) {  // uniform
-      const int l = __builtin_ctzll(todo);
-      const int vv = __shfl(v, l, 64);
-      const uint64_t same = __ballot(mine && v == vv);
-      todo &= ~same;
-      if ((same & (same - 1)) == 0)
-        add_row<BF16>(a, t0 + l, vv, lane, c_begin, c_end);  // alone in the window: its 16-bit values go as they are
-      else
-        add_rows_grouped<BF16>(a, t0, same, vv, lane, c_begin, c_end);
+  constexpr int kWindow = 64 * NW;
+  for (int64_t w0 = (int64_t)me * kWindow; w0 < rows; w0 += (int64_t)per * kWindow) {
+    const int t0 = (int)w0;
+    int v[NW];
+    bool mine[NW];
+    uint64_t todo[NW];
+#pragma unroll
+    for (int k = 0; k < NW; k++) {
+      const int t = t0 + 64 * k + lane;
+      v[k] = t < rows ? a.indices[t] : -1;
+      mine[k] = v[k] >= 0 && v[k] < a.vocab && v[k] != a.padding_idx && (!DIE || (v[k] & 7) == die);
+      todo[k] = __ballot(mine[k]);
+    }
+#pragma unroll
+    for (int k0 = 0; k0 < NW; k0++) {
+      while (todo[k0]) {  // uniform
+        const int l = __builtin_ctzll(todo[k0]);
+        const int vv = __shfl(v[k0], l, 64);
+        uint64_t same[NW];
+        int count = 0;
+#pragma unroll
+        for (int k = 0; k < NW; k++) {
+          same[k] = k >= k0 ? __ballot(mine[k] && v[k] == vv) & todo[k] : 0ull;  // earlier sub-windows are done
+          todo[k] &= ~same[k];
+          count += __popcll(same[k]);
+        }
+        if (count == 1)
+          add_row<BF16>(a, t0 + 64 * k0 + l, vv, lane, c_begin, c_end);  // alone in the window: its 16-bit values go as they are
+        else
+          add_rows_grouped<BF16, NW>(a, t0, same, vv, lane, c_begin, c_end);
+      }
     }
   }
 }

@@ -73,6 +73,13 @@ def test_embedding_bwd_accumulates_skips_and_respects_the_row_count(split):
     run_case(250, 128, 40, "f16", seed=8, split=split, padding_idx=int(ids[1]), init=True, cap=400, ids=ids)
 
 
+@pytest.mark.parametrize("split", ["default", "merged_no_die_split"])
+@pytest.mark.parametrize("dtype,vocab", [("f16", 30522), ("bf16", 997)])
+def test_embedding_bwd_large_batch_uses_wide_windows(dtype, vocab, split):
+    """From 2^17 rows on the workgroups look at 256 tokens at a time (four ids per lane)."""
+    run_case(140001, 64, vocab, dtype, seed=17, split=split)
+
+
 def test_embedding_bwd_one_hot_row_all_tokens_collide():
     """Every token has the same id: the worst case for the atomics."""
     ids = np.full(2000, 17, dtype=np.int32)
