@@ -213,3 +213,35 @@ def test_dropout_bert_large_batch_sampled():
         for name, got, want in zip(("dq", "dk", "dv"), (db.dq, db.dk, db.dv), g_ref):
             rel = np.abs(to_f64(got[sl]) - want).max() / max(np.abs(want).max(), G_FLOOR)
             assert rel <= G_TOL, f"sequence {i} {name}: {rel:.3e}"
+
+
+def test_dropout_large_batch_bf16_sampled():
+    """Workload 5 (2048 sequences, 12 heads, bf16) with p = 0.1 at the benchmark's launch
+    configuration; a sample of sequences with more than one token is checked against the
+    oracle, each with the mask the oracle generates for its start row."""
+    b = wl.make_workload(5)
+    p, seed = 0.1, 55
+    db = DeviceBatch(b, True)
+    db.fwd(dropout=(p, seed))
+    db.bwd(reuse_schedule=True, dropout=(p, seed))
+    torch.cuda.synchronize()
+    for t_ in (db.o, db.dq, db.dk, db.dv, db.lse):
+        assert not torch.isnan(t_).any(), "rows left unwritten"
+    cu, h, L = b["cu_seqlens"], b["heads"], b["lengths"]
+    rng = np.random.default_rng(6)
+    cand = [i for i in rng.choice(len(L), 40, replace=False).tolist() if L[i] > 1][:10]
+    pick = sorted(set(cand) | {int(L.argmax()), len(L) - 1 if L[-1] > 1 else int(L.argmax())})
+    x = oracle_inputs(b)
+    c, thr = dm.keep_scale(p), dm.threshold(p)
+    for i in pick:
+        sl = slice(int(cu[i]), int(cu[i + 1]))
+        n = int(L[i])
+        m = [(dm.random_bytes(int(cu[i]), h, n, n, seed) >= thr).astype(np.uint8)]
+        cu1 = np.array([0, n], dtype=np.int32)
+        o_ref, _ = oracle.fwd_dropout(x["q"][sl], x["k"][sl], x["v"][sl], cu1, b["scale"], m, c)
+        g_ref = oracle.bwd_dropout(x["q"][sl], x["k"][sl], x["v"][sl], x["do"][sl], cu1, b["scale"], m, c)
+        err = np.abs(to_f64(db.o[sl]) - o_ref)
+        assert (err <= O_TOL + ulp_half(o_ref, "bf16")).all(), f"sequence {i}: {err.max():.3e}"
+        for name, got, want in zip(("dq", "dk", "dv"), (db.dq, db.dk, db.dv), g_ref):
+            rel = np.abs(to_f64(got[sl]) - want).max() / max(np.abs(want).max(), G_FLOOR)
+            assert rel <= G_TOL, f"sequence {i} {name}: {rel:.3e}"
