@@ -27,11 +27,12 @@ from . import dropout_mask as dm
 LN_TAG = 0x4C4E  # third counter word of the LayerNorm mask's generator calls
 
 
-def ln_keep_mask(rows: int, hidden: int, p: float, seed: int) -> np.ndarray:
-    """[rows, hidden] uint8, 1 = kept.  Element (t, c) reads byte (c & 15) - byte c & 3 of
-    word (c >> 2) & 3 - of the call with counter (c >> 4, t, LN_TAG, 0) and the seed as key;
-    kept iff that byte >= round(256 p)."""
-    t, c = np.meshgrid(np.arange(rows, dtype=np.int64), np.arange(hidden, dtype=np.int64), indexing="ij")
+def ln_keep_mask(rows: int, hidden: int, p: float, seed: int, first_row: int = 0) -> np.ndarray:
+    """[rows, hidden] uint8, 1 = kept, for rows first_row .. first_row + rows - 1 of the tensor.
+    Element (t, c) reads byte (c & 15) - byte c & 3 of word (c >> 2) & 3 - of the call with
+    counter (c >> 4, t, LN_TAG, 0) and the seed as key; kept iff that byte >= round(256 p)."""
+    t, c = np.meshgrid(np.arange(first_row, first_row + rows, dtype=np.int64),
+                       np.arange(hidden, dtype=np.int64), indexing="ij")
     ctr = np.stack([c >> 4, t, np.full_like(t, LN_TAG), np.zeros_like(t)], axis=-1).astype(np.uint32)
     out = dm.philox4x32_10(ctr, (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))
     word = np.take_along_axis(out, ((c >> 2) & 3)[..., None], axis=-1)[..., 0]

@@ -92,6 +92,7 @@ def test_mask_bytes_looked_up_by_hand():
     # column 15 of row 0: call (0, 0, tag, 0), word 3, byte 3
     out = dm.philox4x32_10(np.array([[0, 0, ln.LN_TAG, 0]], dtype=np.uint32), key)[0]
     assert m[0, 15] == (((int(out[3]) >> 24) & 0xFF) >= 128)
+    assert np.array_equal(ln.ln_keep_mask(3, 64, 0.5, seed, first_row=5), m[5:8])
     big = ln.ln_keep_mask(300, 1024, 0.1, 1)
     pk = 1 - 26 / 256
     assert abs(big.mean() - pk) < 5 * np.sqrt(pk * (1 - pk) / big.size)
