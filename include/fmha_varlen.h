@@ -17,6 +17,12 @@
  * gives the "after the producer, before the consumer" guarantee the paper
  * needs events for.
  *
+ * Besides the attention calls the library holds the operations the paper places around
+ * them on the unpadded storage, each documented where it is declared: dropout on the
+ * attention probabilities, the padded <-> unpadded conversions (Sections IV-A-1, IV-B-2),
+ * the fused Dropout + Add + LayerNorm (Section IV-C-1) and the embedding backward
+ * (Section IV-C-3).
+ *
  * Conventions
  *   - Every pointer named "device" is GPU memory owned by the caller; the
  *     library never allocates, frees or copies to the host, and never
