@@ -297,11 +297,10 @@ int run_fwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dr
     else
       fmha::fmha_fwd_kernel<__bf16, false><<<grid, fmha::kThreads, 0, st>>>(a);
   } else {
-    const unsigned grid2 = grid_for(p, 2);
     if (p->dtype == FMHA_F16)
-      fmha::fmha_fwd_kernel<_Float16, true><<<grid2, fmha::kThreads, 0, st>>>(a);
+      fmha::fmha_fwd_kernel<_Float16, true><<<grid, fmha::kThreads, 0, st>>>(a);
     else
-      fmha::fmha_fwd_kernel<__bf16, true><<<grid2, fmha::kThreads, 0, st>>>(a);
+      fmha::fmha_fwd_kernel<__bf16, true><<<grid, fmha::kThreads, 0, st>>>(a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FMHA_ERR_HIP, "forward launch failed: %s", hipGetErrorString(e));

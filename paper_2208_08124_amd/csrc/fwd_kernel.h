@@ -156,8 +156,8 @@ __device__ __forceinline__ void fwd_block(FwdAcc& acc, const uint16_t* sK, const
 }
 
 template <typename T, bool DROP>
-__global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void fmha_fwd_kernel(const FwdArgs a) {
-  constexpr int kPerCu = DROP ? 2 : 3;  // workgroups per compute unit (the launcher's grid assumes it)
+__global__ __launch_bounds__(kThreads, 3) void fmha_fwd_kernel(const FwdArgs a) {
+  constexpr int kPerCu = 3;  // workgroups per compute unit (the launcher's grid assumes it)
   __shared__ __align__(1024) uint16_t ring[kFwdStages][2][kTileElems];  // [stage][K|V]
 
   const int tid = threadIdx.x;
