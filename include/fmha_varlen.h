@@ -118,6 +118,26 @@ size_t fmha_varlen_workspace_size(int32_t batch, int32_t total_tokens, int32_t h
 int fmha_varlen_fwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
                     void* o, float* lse, void* stream);
 
+/* fmha_varlen_fwd for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the tile list lives in a
+ * device array built into the library instead of a caller workspace, and the call makes no
+ * hipMalloc / hipFree and calls no allocating routine.  p->workspace and
+ * p->workspace_bytes are ignored; everything else (arguments, results, error codes) is as
+ * for fmha_varlen_fwd, whose kernels it shares.
+ *   - Limit: fmha_varlen_workspace_size(batch, total_tokens, heads, 0) must not exceed
+ *     fmha_varlen_static_scratch_bytes() (1 MiB: about 65 000 tiles); larger batches are
+ *     rejected with FMHA_ERR_WORKSPACE and nothing is launched.
+ *   - Every GPU the library runs on holds its own copy of that array until the process
+ *     ends; its address is looked up on the first call on a device.
+ *   - All calls on one GPU share the array, which keeps the previous call's tile list:
+ *     every call rebuilds the list before using it (FMHA_FLAG_REUSE_SCHEDULE reuses the
+ *     list the previous such call on this GPU left there), and calls that overlap in time
+ *     on one GPU (other streams, other threads) race on it - serialise them, or use
+ *     fmha_varlen_fwd with separate workspaces. */
+size_t fmha_varlen_static_scratch_bytes(void);
+int fmha_varlen_fwd_static(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
+                           void* o, float* lse, void* stream);
+
 /* Backward: given dO, recompute the probabilities from q, k and lse and write
  *   dV = P^T dO,  dP = dO V^T,  dS = P o (dP - rowsum(dO o O)),
  *   dQ = scale dS K,  dK = scale dS^T Q.

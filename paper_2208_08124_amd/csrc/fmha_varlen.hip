@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/fmha_varlen.h"
 #include "host_error.h"
@@ -181,6 +182,33 @@ int drop_args(const fmha_dropout_t* d, bool required, fmha::DropArgs* out) {
   return FMHA_OK;
 }
 
+// ---- the library's own scratch memory, for fmha_varlen_fwd_static -----------------
+// `scratch` is a device array: in host code its name is only a handle for
+// hipGetSymbolAddress, never an address to hand to a kernel.  Every GPU holds its own copy
+// at its own address, looked up once per device (with that device current) and kept.
+constexpr size_t kStaticScratchBytes = (size_t)1 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(FMHA_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return fail(FMHA_ERR_HIP, "device index %d is outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(FMHA_ERR_HIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return FMHA_OK;
+}
+
 int run_fwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dropout, const void* q,
             const void* k, const void* v, void* o, float* lse, void* stream);
 int run_bwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dropout, const void* q,
@@ -217,6 +245,28 @@ int fmha_varlen_fwd(const fmha_varlen_params_t* p, const void* q, const void* k,
 int fmha_varlen_fwd_dropout(const fmha_varlen_params_t* p, const fmha_dropout_t* dropout, const void* q,
                             const void* k, const void* v, void* o, float* lse, void* stream) {
   return run_fwd(p, dropout, true, q, k, v, o, lse, stream);
+}
+
+size_t fmha_varlen_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int fmha_varlen_fwd_static(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,
+                           void* o, float* lse, void* stream) {
+  if (!p) return fail(FMHA_ERR_INVALID_ARG, "params is null");
+  if (p->batch < 0 || p->total_tokens < 0 || p->heads <= 0)
+    return fail(FMHA_ERR_INVALID_ARG, "batch=%d, total_tokens=%d, heads=%d: invalid sizes", p->batch, p->total_tokens, p->heads);
+  const size_t need = fmha_varlen_workspace_size(p->batch, p->total_tokens, p->heads, 0);
+  if (need > kStaticScratchBytes)
+    return fail(FMHA_ERR_WORKSPACE,
+                "a batch of %d sequences and %d tokens needs %zu bytes for its tile list, the built-in scratch "
+                "holds %zu: use fmha_varlen_fwd with a workspace",
+                p->batch, p->total_tokens, need, kStaticScratchBytes);
+  void* ptr = nullptr;
+  int rc = static_scratch(&ptr);
+  if (rc) return rc;
+  fmha_varlen_params_t local = *p;
+  local.workspace = ptr;
+  local.workspace_bytes = kStaticScratchBytes;
+  return run_fwd(&local, nullptr, false, q, k, v, o, lse, stream);
 }
 
 int fmha_varlen_bwd(const fmha_varlen_params_t* p, const void* q, const void* k, const void* v,

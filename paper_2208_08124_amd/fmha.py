@@ -25,6 +25,7 @@ FMHA_EMB_PLAIN_SPLIT = 2
 FMHA_EMB_NO_DIE_SPLIT = 4
 
 EXPORTS = ("fmha_varlen_workspace_size", "fmha_varlen_fwd", "fmha_varlen_bwd",
+           "fmha_varlen_fwd_static", "fmha_varlen_static_scratch_bytes",
            "fmha_varlen_fwd_dropout", "fmha_varlen_bwd_dropout", "fmha_dropout_keep_mask",
            "fmha_unpad_indices_host", "fmha_unpad_indices", "fmha_gather_rows", "fmha_scatter_rows",
            "fmha_dropout_add_ln_fwd", "fmha_dropout_add_ln_bwd", "fmha_dropout_add_ln_bwd_workspace_size",
@@ -82,6 +83,10 @@ def lib():
         L.fmha_varlen_workspace_size.restype = ctypes.c_size_t
         L.fmha_varlen_fwd.argtypes = [ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp]
         L.fmha_varlen_fwd.restype = ctypes.c_int
+        L.fmha_varlen_fwd_static.argtypes = [ctypes.POINTER(Params), vp, vp, vp, vp, vp, vp]
+        L.fmha_varlen_fwd_static.restype = ctypes.c_int
+        L.fmha_varlen_static_scratch_bytes.argtypes = []
+        L.fmha_varlen_static_scratch_bytes.restype = ctypes.c_size_t
         L.fmha_varlen_bwd.argtypes = [ctypes.POINTER(Params)] + [vp] * 10
         L.fmha_varlen_bwd.restype = ctypes.c_int
         dp = ctypes.POINTER(Dropout)
@@ -174,8 +179,9 @@ def _params(q, cu_seqlens, max_seqlen, scale, workspace, seqused, cu_seqlens_hos
     if seqused is not None:
         assert seqused.dtype == torch.int32 and seqused.is_cuda and seqused.is_contiguous()
         p.seqused = seqused.data_ptr()
-    p.workspace = workspace.data_ptr()
-    p.workspace_bytes = workspace.numel() * workspace.element_size()
+    if workspace is not None:
+        p.workspace = workspace.data_ptr()
+        p.workspace_bytes = workspace.numel() * workspace.element_size()
     return p, keep
 
 
@@ -202,6 +208,17 @@ def fmha_varlen_fwd(q, k, v, cu_seqlens, max_seqlen, scale, o, lse, workspace, *
     else:
         d = _dropout(dropout)
         _check(lib().fmha_varlen_fwd_dropout(ctypes.byref(p), ctypes.byref(d), *ptrs))
+    del keep
+
+
+def fmha_varlen_fwd_static(q, k, v, cu_seqlens, max_seqlen, scale, o, lse, *,
+                           seqused=None, cu_seqlens_host=None, reuse_schedule=False):
+    """fmha_varlen_fwd without a workspace: the tile list lives in the library's own device array."""
+    p, keep = _params(q, cu_seqlens, max_seqlen, scale, None, seqused, cu_seqlens_host, reuse_schedule)
+    p.q_stride, p.k_stride, p.v_stride, p.o_stride = map(_tok_stride, (q, k, v, o))
+    assert lse.dtype == torch.float32 and lse.is_contiguous() and lse.numel() == q.shape[0] * q.shape[1]
+    _check(lib().fmha_varlen_fwd_static(ctypes.byref(p), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                        lse.data_ptr(), _stream()))
     del keep
 
 

@@ -131,6 +131,21 @@ def test_backward_rejects_conflicting_pass_flags():
     assert rc == fmha.FMHA_ERR_INVALID_ARG and "exclude" in fmha.last_error()
 
 
+def test_static_forward_rejects_oversize_batches_on_the_host():
+    """The size check of the allocation-free forward precedes every device call."""
+    from paper_2208_08124_amd import fmha
+    fk = Fake()
+    limit = fmha.lib().fmha_varlen_static_scratch_bytes()
+    assert limit == 1 << 20
+    p = fmha.Params()
+    p.batch, p.total_tokens, p.heads, p.head_dim, p.max_seqlen = 70000, 70000, 1, 64, 1
+    p.dtype, p.scale, p.cu_seqlens = fmha.FMHA_F16, 0.125, fk.p
+    assert fmha.fmha_varlen_workspace_size(p.batch, p.total_tokens, p.heads, False) > limit
+    rc = fmha.lib().fmha_varlen_fwd_static(ctypes.byref(p), fk.p, fk.p, fk.p, fk.p, fk.p, None)
+    assert rc == fmha.FMHA_ERR_WORKSPACE and "built-in scratch" in fmha.last_error()
+    assert fmha.lib().fmha_varlen_fwd_static(None, fk.p, fk.p, fk.p, fk.p, fk.p, None) == fmha.FMHA_ERR_INVALID_ARG
+
+
 def test_struct_layouts_against_the_c_compiler(tmp_path):
     """sizeof / offsetof of every struct in the header as gcc sees them, against the ctypes mirrors."""
     import subprocess
