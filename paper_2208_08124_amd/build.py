@@ -11,6 +11,9 @@ LIB = os.path.join(HERE, "libfmha_varlen.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the item feed's claims are single-lane atomics whose answers are needed much later:
+    # the compiler's wave-wide combining of atomics would wait for them on the spot
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
     "-Wall", "-Wno-unused-value",
 ]
 

@@ -12,6 +12,7 @@
 #include "../../include/fmha_varlen.h"
 #include "host_error.h"
 #include "bwd_kernels.h"
+#include "fwd64_kernel.h"
 #include "fwd_kernel.h"
 #include "keep_mask_kernel.h"
 #include "schedule.h"
@@ -45,16 +46,18 @@ int64_t tile_capacity(int64_t batch, int64_t total_tokens) {
 
 struct Workspace {
   int32_t* count;
+  uint32_t* feed;  // the item feed's counters (item_feed.h)
   fmha::TileItem* list;
   float* dsum;
   float* lse2;
-  size_t count_off, list_off, dsum_off, lse2_off, bytes_fwd, bytes_bwd;
+  size_t count_off, feed_off, list_off, dsum_off, lse2_off, bytes_fwd, bytes_bwd;
 };
 
 Workspace carve(void* base, int64_t batch, int64_t total_tokens, int64_t heads) {
   Workspace w;
   w.count_off = 0;
-  w.list_off = kAlign;
+  w.feed_off = kAlign;
+  w.list_off = w.feed_off + sizeof(uint32_t) * fmha::kFeedWords;
   const size_t list_bytes = sizeof(fmha::TileItem) * (size_t)(tile_capacity(batch, total_tokens) + 1);
   w.dsum_off = round_up(w.list_off + list_bytes, kAlign);
   w.bytes_fwd = w.dsum_off;
@@ -64,6 +67,7 @@ Workspace carve(void* base, int64_t batch, int64_t total_tokens, int64_t heads) 
   w.bytes_bwd = w.lse2_off + stat_bytes;
   char* b = static_cast<char*>(base);
   w.count = reinterpret_cast<int32_t*>(b + w.count_off);
+  w.feed = reinterpret_cast<uint32_t*>(b + w.feed_off);
   w.list = reinterpret_cast<fmha::TileItem*>(b + w.list_off);
   w.dsum = reinterpret_cast<float*>(b + w.dsum_off);
   w.lse2 = reinterpret_cast<float*>(b + w.lse2_off);
@@ -152,7 +156,8 @@ unsigned grid_for(const fmha_varlen_params_t* p, int per_cu) {
 int launch_schedule(const fmha_varlen_params_t* p, const Workspace& w, hipStream_t st) {
   if (p->flags & FMHA_FLAG_REUSE_SCHEDULE) return FMHA_OK;
   const int cap = (int)tile_capacity(p->batch, p->total_tokens);
-  fmha::schedule_kernel<<<1, fmha::kSchedThreads, 0, st>>>(p->cu_seqlens, p->seqused, p->batch, w.count, w.list, cap);
+  fmha::schedule_kernel<<<1, fmha::kSchedThreads, 0, st>>>(p->cu_seqlens, p->seqused, p->batch, w.count, w.list, cap,
+                                                          w.feed);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FMHA_ERR_HIP, "schedule launch failed: %s", hipGetErrorString(e));
   return FMHA_OK;
@@ -166,6 +171,33 @@ fmha::Problem problem_of(const fmha_varlen_params_t* p, const Workspace& w) {
   pb.total_tokens = p->total_tokens;
   pb.scale = p->scale;
   return pb;
+}
+
+// Upper bound on the number of (tile, head) items, from host-visible sizes only.
+int64_t items_bound(const fmha_varlen_params_t* p) {
+  int64_t tiles = tile_capacity(p->batch, p->total_tokens);
+  if (p->max_seqlen > 0) {
+    const int64_t per_seq = (p->max_seqlen + fmha::kTileRows - 1) / fmha::kTileRows;
+    if (per_seq * p->batch < tiles) tiles = per_seq * p->batch;
+  }
+  return tiles * p->heads;
+}
+
+// Persistent grid of `per_cu` workgroups per compute unit (a multiple of 8, never more than
+// there can be items), and the item feed's chunk size for it: about 24 chunks per workgroup
+// on large batches, single items on small ones.
+unsigned feed_grid(const fmha_varlen_params_t* p, int per_cu, const Workspace& w, fmha::FeedArgs* feed) {
+  const int64_t items = items_bound(p);
+  int64_t g = (int64_t)compute_units() * per_cu;
+  if (g > items) g = items;
+  g = (g + 7) / 8 * 8;
+  if (g < 8) g = 8;
+  int64_t chunk = items / (g * 24);
+  if (chunk < 1) chunk = 1;
+  if (chunk > 256) chunk = 256;
+  feed->counters = w.feed;
+  feed->chunk = (int32_t)chunk;
+  return (unsigned)g;
 }
 
 // Dropout arguments for the kernels; d == nullptr means no dropout.
@@ -333,6 +365,7 @@ int run_fwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dr
   Workspace w = carve(p->workspace, p->batch, p->total_tokens, p->heads);
   if ((rc = launch_schedule(p, w, st))) return rc;
   a.pb = problem_of(p, w);
+  a.feed = fmha::FeedArgs{w.feed, 1};
   a.q = static_cast<const uint16_t*>(q);
   a.k = static_cast<const uint16_t*>(k);
   a.v = static_cast<const uint16_t*>(v);
@@ -342,10 +375,12 @@ int run_fwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dr
   a.drop = da;
   // p = 0 (threshold 0) keeps everything: the plain kernels serve it
   if (da.thr == 0) {
+    // persistent: 4 workgroups of 2 wavefronts per compute unit
+    const unsigned grid64 = feed_grid(p, 4, w, &a.feed);
     if (p->dtype == FMHA_F16)
-      fmha::fmha_fwd_kernel<_Float16, false><<<grid, fmha::kThreads, 0, st>>>(a);
+      fmha::fmha_fwd64_kernel<_Float16><<<grid64, fmha::kF64Threads, 0, st>>>(a);
     else
-      fmha::fmha_fwd_kernel<__bf16, false><<<grid, fmha::kThreads, 0, st>>>(a);
+      fmha::fmha_fwd64_kernel<__bf16><<<grid64, fmha::kF64Threads, 0, st>>>(a);
   } else {
     if (p->dtype == FMHA_F16)
       fmha::fmha_fwd_kernel<_Float16, true><<<grid, fmha::kThreads, 0, st>>>(a);
@@ -387,6 +422,7 @@ int run_bwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dr
   Workspace w = carve(p->workspace, p->batch, p->total_tokens, p->heads);
   if ((rc = launch_schedule(p, w, st))) return rc;
   a.pb = problem_of(p, w);
+  a.feed = fmha::FeedArgs{w.feed, 1};
   a.drop = da;
   a.q = static_cast<const uint16_t*>(q);
   a.k = static_cast<const uint16_t*>(k);

@@ -2,6 +2,8 @@
 #pragma once
 #include <stdint.h>
 
+#include "item_feed.h"
+
 namespace fmha {
 
 constexpr int kHeadDim = 64;
@@ -37,6 +39,7 @@ struct DropArgs {
 struct FwdArgs {
   Problem pb;
   DropArgs drop;
+  FeedArgs feed;
   const uint16_t *q, *k, *v;
   uint16_t* o;
   float* lse;  // [H, T]
@@ -46,6 +49,7 @@ struct FwdArgs {
 struct BwdArgs {
   Problem pb;
   DropArgs drop;
+  FeedArgs feed;
   const uint16_t *q, *k, *v, *o, *d_o;
   const float* lse;  // [H, T]
   float* dsum;       // [H, T] rowsum(dO o O), workspace (written by the dQ pass)

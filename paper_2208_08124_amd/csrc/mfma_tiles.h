@@ -20,6 +20,7 @@ namespace fmha {
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((__vector_size__(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -53,6 +54,15 @@ struct Op<_Float16> {
     typedef _Float16 h2 __attribute__((ext_vector_type(2)));
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, a), __builtin_bit_cast(h2, b), acc, false);
   }
+  // Every element of acc + the sum of this lane's four 16-bit values in w, on the matrix core:
+  // v_mfma_f32_4x4x4_16b with an A operand of ones gives D[i][j] = C[i][j] + sum_k B[k][j],
+  // and a lane holds all four k of its column j whatever the block arrangement.  (Row sums
+  // this way cost 8 cycles of the matrix pipe per four values and none of the vector ALU.)
+  static __device__ __forceinline__ f32x4 sum4(u32x2 w, f32x4 acc) {
+    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+    const u32x2 ones = {0x3c003c00u, 0x3c003c00u};
+    return __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(h4, ones), __builtin_bit_cast(h4, w), acc, 0, 0, 0);
+  }
 };
 
 template <>
@@ -74,6 +84,11 @@ struct Op<__bf16> {
   static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
     typedef __bf16 b2 __attribute__((ext_vector_type(2)));
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(b2, a), __builtin_bit_cast(b2, b), acc, false);
+  }
+  static __device__ __forceinline__ f32x4 sum4(u32x2 w, f32x4 acc) {
+    typedef short s4 __attribute__((ext_vector_type(4)));
+    const u32x2 ones = {0x3f803f80u, 0x3f803f80u};
+    return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(s4, ones), __builtin_bit_cast(s4, w), acc, 0, 0, 0);
   }
 };
 
@@ -169,6 +184,10 @@ struct ColRead {
 // The instruction is issued from inline assembly so that the compiler does
 // not serialise every later LDS read behind it; completion is awaited with
 // explicit s_waitcnt vmcnt(n) (vector memory loads complete in issue order).
+// m0 is not named as a clobber: it is a reserved register to the compiler (which rejects
+// it in clobber lists with a warning) - the compiler never keeps a value of its own in m0
+// across other instructions, it writes m0 directly ahead of each instruction of its own
+// that reads it.
 // ---------------------------------------------------------------------------
 static __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
@@ -328,6 +347,38 @@ __device__ __forceinline__ void store_rows(const f32x16 (&x)[2], float scale, ui
                                                     ((chunk ^ swz(row)) << 3));
     if (row < n_rows) *reinterpret_cast<u32x4*>(ob + ((uint32_t)row * row_bytes + 16u * chunk)) = w;
   }
+}
+
+// The same through a 4 KB scratch tile that belongs to the calling wavefront alone (32 rows of
+// 128 bytes, 16-byte chunk c of row r at position c ^ swz(r)).  The scratch may be reused
+// right after the call: the wavefront's LDS operations execute in program order.
+template <typename T>
+__device__ __forceinline__ void store_rows32(const f32x16 (&x)[2], float scale, uint16_t* scratch,
+                                             uint16_t* out_tensor, int64_t out_offset, int64_t out_stride,
+                                             int n_rows) {
+  const int lane = lane_id();
+  const int g = lane >> 5, ln = lane & 31;
+  uint16_t* wr = scratch + ln * 64 + 4 * g;
+  const int sw = swz(ln);
+#pragma unroll
+  for (int cb = 0; cb < 2; cb++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      u32x2 w = {Op<T>::pack2(x[cb][4 * j] * scale, x[cb][4 * j + 1] * scale),
+                 Op<T>::pack2(x[cb][4 * j + 2] * scale, x[cb][4 * j + 3] * scale)};
+      *reinterpret_cast<u32x2*>(wr + (((4 * cb + j) ^ sw) << 3)) = w;
+    }
+  __builtin_amdgcn_wave_barrier();
+  const int chunk = lane & 7;
+  char* ob = reinterpret_cast<char*>(out_tensor + uniform_i64(out_offset));
+  const uint32_t row_bytes = (uint32_t)out_stride * 2u;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int row = 8 * i + (lane >> 3);
+    const u32x4 w = *reinterpret_cast<const u32x4*>(scratch + row * 64 + ((chunk ^ swz(row)) << 3));
+    if (row < n_rows) *reinterpret_cast<u32x4*>(ob + ((uint32_t)row * row_bytes + 16u * chunk)) = w;
+  }
+  __builtin_amdgcn_wave_barrier();
 }
 
 }  // namespace fmha

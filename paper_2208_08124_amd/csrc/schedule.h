@@ -22,9 +22,11 @@ __device__ __forceinline__ int sched_bucket(int nkeys) {
 __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* __restrict__ cu,
                                                                  const int32_t* __restrict__ seqused,
                                                                  int batch, int32_t* count,
-                                                                 TileItem* list, int cap) {
+                                                                 TileItem* list, int cap, uint32_t* feed_counters) {
   __shared__ int cursor[kSchedBuckets];
   const int tid = threadIdx.x;
+  if (tid < kFeedWords) feed_counters[tid] = 0u;  // the item feed's counters start at zero
+  static_assert(kFeedWords <= kSchedThreads, "one thread per word");
   if (tid < kSchedBuckets) cursor[tid] = 0;
   __syncthreads();
   // The thread's first sequence stays in registers for the second sweep (one memory

@@ -355,6 +355,50 @@ def test_degenerate_batches():
         run(b, True)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("growth", [24.0, 150.0, -150.0])
+def test_scores_that_grow_along_the_keys(dtype, growth):
+    """The forward kernel takes its exponent against the largest score among a row's first 32
+    keys and falls back to a running maximum when a row's sum overflows.  Here the scores
+    climb (or fall) by `growth` units over the sequence, far beyond what the 16-bit
+    probabilities (2^16 for f16) or the fp32 sums (2^128) hold relative to the first block, so
+    without the fallback the rising cases come out non-finite."""
+    lengths = [512, 300, 70, 33, 129]
+    heads = 3
+    b = wl.make_batch(lengths, heads, dtype, seed=77)
+    rng = np.random.default_rng(78)
+    t = b["total_tokens"]
+    q = rng.standard_normal((t, heads, 64)).astype(np.float32) * 0.5 + 1.0
+    k = rng.standard_normal((t, heads, 64)).astype(np.float32) * 0.5
+    for i, L in enumerate(lengths):
+        r0 = int(b["cu_seqlens"][i])
+        # q . k gains about 64 * ramp, the score 0.125 * that
+        k[r0:r0 + L] += (growth / 8.0) * (np.arange(L, dtype=np.float32) / max(L - 1, 1))[:, None, None]
+    to_bits = (lambda x: x.astype(np.float16).view(np.uint16)) if dtype == "f16" else wl.f32_to_bf16_bits
+    b["q"], b["k"] = to_bits(q), to_bits(k)
+    # gradients in f16 only: the common offset this adds to the keys multiplies the rounding
+    # of the stored O inside D = rowsum(dO * O), which in bf16 alone is worth 1.3e-2 of max|dQ|
+    run(b, dtype == "f16")
+
+
+def test_hand_out_counters_are_left_zero():
+    """Every kernel that draws work items from the counters in the workspace must leave them
+    zero for the next one: check after a forward and after a backward, with enough items that
+    chunks are claimed dynamically."""
+    b = wl.make_batch([512] * 40 + [100] * 30, 16, "f16", seed=61)
+    db = DeviceBatch(b, True)
+    _, c_off, l_off = fmha.fmha_varlen_schedule_info(b["batch"], b["total_tokens"])
+    feed = slice(c_off + 256, l_off)
+    db.fwd()
+    torch.cuda.synchronize()
+    assert l_off - (c_off + 256) == 2048 and not db.ws[feed].any()
+    first = db.o.clone()
+    db.fwd(reuse_schedule=True)
+    db.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    assert not db.ws[feed].any() and torch.equal(db.o, first)
+
+
 def test_two_runs_are_bit_identical():
     b = wl.make_workload(4)
     a_, b_ = DeviceBatch(b, True), DeviceBatch(b, True)
