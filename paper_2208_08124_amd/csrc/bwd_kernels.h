@@ -121,16 +121,17 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const Bw
     a.dsum[(int64_t)heads * a.pb.total_tokens] = 0.f;
   }
 
-  // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
-  // next item is fetched while the current one is computed.
-  TileItem ti_next = load_tile(a.pb, ((int)blockIdx.x < n_items ? (int)blockIdx.x : 0) / heads);
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  // Persistent workgroups that draw their items from the feed (item_feed.h); the record of
+  // the next item is fetched while the current one is computed.
+  __shared__ uint32_t mailbox;
+  ItemFeed feed;
+  int item = feed.init(a.feed, blockIdx.x, gridDim.x);
+  int item1 = feed.next();
+  TileItem ti_next = load_tile(a.pb, (item < n_items ? item : 0) / heads);
+  while (item < n_items) {
     const int head = item % heads;
     const TileItem ti = ti_next;
-    {
-      const int nxt = item + gridDim.x;
-      ti_next = load_tile(a.pb, (nxt < n_items ? nxt : item) / heads);
-    }
+    ti_next = load_tile(a.pb, (item1 < n_items ? item1 : item) / heads);
     const int r0 = ti.r0, len = ti.len, nk = ti.nk;
     const int qrow = ti.row0 + 32 * wave + ln;
     const bool wave_on = ti.row0 + 32 * wave < len;
@@ -233,7 +234,11 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const Bw
       }
       stage = stage == kBwdStages - 1 ? 0 : stage + 1;
     }
+    feed.publish(&mailbox);
     __syncthreads();  // the ring is free for the next item
+    feed.receive(&mailbox);
+    const int item2 = feed.next();
+    feed.request(a.feed);
 
     // The row statistics for pass 2 are stored here rather than where they are
     // computed: a store issued ahead of the key loop would have to be acknowledged
@@ -253,7 +258,10 @@ __global__ __launch_bounds__(kThreads, DROP ? 2 : 3) void bwd_dq_kernel(const Bw
       store_rows<T>(dq, a.pb.scale, &ring[kBwdStages - 1][0][0], wave, a.dq,
                     (int64_t)(r0 + ti.row0 + 32 * wave) * a.dq_stride + head * kHeadDim, a.dq_stride,
                     len - (ti.row0 + 32 * wave));
+    item = item1;
+    item1 = item2;
   }
+  feed.finish(a.feed, gridDim.x);
 }
 
 // ------------------------------------------------------------ pass 2: dK, dV
@@ -366,16 +374,17 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
   const uint32_t q_lane = (dl.row * (uint32_t)a.q_stride + dl.chunk * 8) * 2u;  // bytes
   const uint32_t g_lane = (dl.row * (uint32_t)a.do_stride + dl.chunk * 8) * 2u;
 
-  // Persistent workgroups: workgroup b takes items b, b + grid, ...; the record of the
-  // next item is fetched while the current one is computed.
-  TileItem ti_next = load_tile(a.pb, ((int)blockIdx.x < n_items ? (int)blockIdx.x : 0) / heads);
-  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+  // Persistent workgroups that draw their items from the feed (item_feed.h); the record of
+  // the next item is fetched while the current one is computed.
+  __shared__ uint32_t mailbox;
+  ItemFeed feed;
+  int item = feed.init(a.feed, blockIdx.x, gridDim.x);
+  int item1 = feed.next();
+  TileItem ti_next = load_tile(a.pb, (item < n_items ? item : 0) / heads);
+  while (item < n_items) {
     const int head = item % heads;
     const TileItem ti = ti_next;
-    {
-      const int nxt = item + gridDim.x;
-      ti_next = load_tile(a.pb, (nxt < n_items ? nxt : item) / heads);
-    }
+    ti_next = load_tile(a.pb, (item1 < n_items ? item1 : item) / heads);
     const int r0 = ti.r0, len = ti.len, nk = ti.nk;
     const int krow = ti.row0 + 32 * wave + ln;      // this lane's key, within the sequence
     const bool wave_on = ti.row0 + 32 * wave < nk;  // wavefront owns at least one live key
@@ -455,7 +464,11 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
       }
       stage = stage == kBwdStages - 1 ? 0 : stage + 1;
     }
+    feed.publish(&mailbox);
     __syncthreads();
+    feed.receive(&mailbox);
+    const int item2 = feed.next();
+    feed.request(a.feed);
 
     // every row of the tile is written: live keys get their gradients, keys
     // masked by seqused get zeros.  dK and dV leave as whole rows, turned around in
@@ -474,7 +487,10 @@ __global__ __launch_bounds__(kThreads, 2) void bwd_dkv_kernel(const BwdArgs a) {
       store_rows<T>(dv, DROP ? a.drop.rp : 1.f, ring[kBwdStages - 2].q, wave, a.dv, tok * a.dv_stride + head * kHeadDim,
                     a.dv_stride, n_rows);
     }
+    item = item1;
+    item1 = item2;
   }
+  feed.finish(a.feed, gridDim.x);
 }
 
 }  // namespace fmha

@@ -156,8 +156,8 @@ unsigned grid_for(const fmha_varlen_params_t* p, int per_cu) {
 int launch_schedule(const fmha_varlen_params_t* p, const Workspace& w, hipStream_t st) {
   if (p->flags & FMHA_FLAG_REUSE_SCHEDULE) return FMHA_OK;
   const int cap = (int)tile_capacity(p->batch, p->total_tokens);
-  fmha::schedule_kernel<<<1, fmha::kSchedThreads, 0, st>>>(p->cu_seqlens, p->seqused, p->batch, w.count, w.list, cap,
-                                                          w.feed);
+  fmha::schedule_kernel<<<1, fmha::kSchedThreads, 0, st>>>(p->cu_seqlens, p->seqused, p->batch, p->total_tokens, w.count,
+                                                          w.list, cap, w.feed);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(FMHA_ERR_HIP, "schedule launch failed: %s", hipGetErrorString(e));
   return FMHA_OK;
@@ -435,24 +435,28 @@ int run_bwd(const fmha_varlen_params_t* p, const fmha_dropout_t* d, bool with_dr
   a.dq = static_cast<uint16_t*>(dq);
   a.dk = static_cast<uint16_t*>(dk);
   a.dv = static_cast<uint16_t*>(dv);
-  const unsigned grid_dq = grid_for(p, 3), grid = grid_for(p, 2);
+  // persistent grids with their own hand-out chunk sizes: 3 workgroups per compute unit for
+  // the dQ pass (2 with dropout), 2 for the dK/dV pass
+  fmha::BwdArgs a_dq = a, a_dkv = a;
+  const unsigned grid_dq = feed_grid(p, da.thr == 0 ? 3 : 2, w, &a_dq.feed);
+  const unsigned grid_dkv = feed_grid(p, 2, w, &a_dkv.feed);
   const bool run_dq = !(p->flags & FMHA_FLAG_BWD_ONLY_DKV);
   const bool run_dkv = !(p->flags & FMHA_FLAG_BWD_ONLY_DQ);
   if (da.thr == 0) {
     if (p->dtype == FMHA_F16) {
-      if (run_dq) fmha::bwd_dq_kernel<_Float16, false><<<grid_dq, fmha::kThreads, 0, st>>>(a);
-      if (run_dkv) fmha::bwd_dkv_kernel<_Float16, false><<<grid, fmha::kThreads, 0, st>>>(a);
+      if (run_dq) fmha::bwd_dq_kernel<_Float16, false><<<grid_dq, fmha::kThreads, 0, st>>>(a_dq);
+      if (run_dkv) fmha::bwd_dkv_kernel<_Float16, false><<<grid_dkv, fmha::kThreads, 0, st>>>(a_dkv);
     } else {
-      if (run_dq) fmha::bwd_dq_kernel<__bf16, false><<<grid_dq, fmha::kThreads, 0, st>>>(a);
-      if (run_dkv) fmha::bwd_dkv_kernel<__bf16, false><<<grid, fmha::kThreads, 0, st>>>(a);
+      if (run_dq) fmha::bwd_dq_kernel<__bf16, false><<<grid_dq, fmha::kThreads, 0, st>>>(a_dq);
+      if (run_dkv) fmha::bwd_dkv_kernel<__bf16, false><<<grid_dkv, fmha::kThreads, 0, st>>>(a_dkv);
     }
   } else {
     if (p->dtype == FMHA_F16) {
-      if (run_dq) fmha::bwd_dq_kernel<_Float16, true><<<grid, fmha::kThreads, 0, st>>>(a);
-      if (run_dkv) fmha::bwd_dkv_kernel<_Float16, true><<<grid, fmha::kThreads, 0, st>>>(a);
+      if (run_dq) fmha::bwd_dq_kernel<_Float16, true><<<grid_dq, fmha::kThreads, 0, st>>>(a_dq);
+      if (run_dkv) fmha::bwd_dkv_kernel<_Float16, true><<<grid_dkv, fmha::kThreads, 0, st>>>(a_dkv);
     } else {
-      if (run_dq) fmha::bwd_dq_kernel<__bf16, true><<<grid, fmha::kThreads, 0, st>>>(a);
-      if (run_dkv) fmha::bwd_dkv_kernel<__bf16, true><<<grid, fmha::kThreads, 0, st>>>(a);
+      if (run_dq) fmha::bwd_dq_kernel<__bf16, true><<<grid_dq, fmha::kThreads, 0, st>>>(a_dq);
+      if (run_dkv) fmha::bwd_dkv_kernel<__bf16, true><<<grid_dkv, fmha::kThreads, 0, st>>>(a_dkv);
     }
   }
   hipError_t e = hipGetLastError();

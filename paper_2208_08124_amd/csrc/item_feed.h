@@ -8,14 +8,15 @@
 // heuristic: nothing depends on it for correctness).
 //
 // Within a class, positions k = i / 8 are handed out in chunks of `chunk` consecutive
-// positions: the first two chunks of every workgroup are fixed (chunk number = its rank in
-// the class, then in mirrored order, so that every workgroup starts with a similar load),
-// all later ones are claimed from a counter per class with an atomic add.  Workgroups that run faster - on a SIMD the older wavefront
-// is favoured, measured 15 against 22 us per item - thereby take more items, and the
-// expensive items, which come first, are never left for the end.  A claim is requested
-// one item before it is needed (its latency never shows) by the first lane of the
-// workgroup and reaches the other wavefronts through a word of LDS at a barrier the kernels
-// have anyway.
+// positions.  The first three chunks of every workgroup are fixed: chunk number = its rank in
+// the class, then the mirrored rank (so that every workgroup starts with a similar load), then
+// the rank again; all later ones are claimed from a counter per class with an atomic add, so
+// that workgroups that run faster - on a SIMD the older wavefront is favoured, measured 15
+// against 22 us per item - take more items, and the expensive items, which come first, are
+// never left for the end.  A claim is requested two items before it is needed (its latency
+// never shows; the first one when the workgroup has finished its first item, so that the
+// claims are ordered by progress and not by launch time) by the first lane of the workgroup
+// and reaches the other wavefronts through a word of LDS at a barrier the kernels have anyway.
 //
 // The counters live in the workspace; the tile-list kernel zeroes them, and every kernel
 // that uses them leaves them zero: the last workgroup to finish clears them (told by exit
@@ -43,28 +44,27 @@ struct FeedArgs {
 struct ItemFeed {
   int cls;           // class of this workgroup
   int kpos, kend;    // next position and end of the current chunk
-  int second;        // first position of the second fixed chunk
-  int dyn_base;      // position at which claimed chunks start
+  int rank, per_class;
   int chunk;
-  int stage;         // chunks started so far
-  int pending;       // start of the next claimed chunk, relative to dyn_base (all wavefronts)
-  bool want;         // the pending claim was used up: request another
+  int stage;         // chunks started so far, minus one
+  int pending;       // start of the next claimed chunk, relative to the end of the fixed ones (all wavefronts)
+  bool want;         // the pending claim was used up (or none was made yet): request another
   uint32_t claimed;  // first lane of the workgroup: the claim last requested
+
+  static constexpr int kFixed = 3;  // chunks per workgroup that are not claimed
 
   // grid must be a multiple of 8.  Returns the workgroup's first item.
   __device__ __forceinline__ int init(const FeedArgs& f, int block, int grid) {
     cls = block & 7;
     chunk = f.chunk;
-    const int per_class = grid >> 3, rank = block >> 3;
-    kpos = chunk * rank;  // the first two chunks of every workgroup are fixed,
+    per_class = grid >> 3;
+    rank = block >> 3;
+    kpos = chunk * rank;
     kend = kpos + chunk;
-    second = chunk * (2 * per_class - 1 - rank);  // the second one in mirrored order
-    dyn_base = 2 * chunk * per_class;
     stage = 0;
     pending = 0;
     claimed = 0;
     want = true;
-    request(f);
     return (kpos++) * kFeedClasses + cls;
   }
   // Request the next chunk if the last one received has been used.  Call it where the
@@ -90,13 +90,15 @@ struct ItemFeed {
   // receive() and then once after each receive(), followed by request().
   __device__ __forceinline__ int next() {
     if (kpos >= kend) {
-      if (stage == 0) {
-        kpos = second;
+      stage++;
+      if (stage == 1) {
+        kpos = chunk * (2 * per_class - 1 - rank);
+      } else if (stage < kFixed) {
+        kpos = chunk * (stage * per_class + rank);
       } else {
-        kpos = dyn_base + pending;
+        kpos = chunk * kFixed * per_class + pending;
         want = true;
       }
-      stage++;
       kend = kpos + chunk;
     }
     return (kpos++) * kFeedClasses + cls;

@@ -17,11 +17,27 @@ __device__ __forceinline__ int sched_bucket(int nkeys) {
   return kSchedBuckets - 1 - b;
 }
 
+// A sequence as the kernels may use it: whatever the device arrays hold, the rows
+// [r0, r0 + len) lie inside the packed tensors of total_tokens rows (arrays that disagree
+// with the sizes the host passed can then only give wrong numbers, never addresses out of
+// range), and at most len keys are attended.
+struct SchedSeq {
+  int r0, len, nk;
+};
+__device__ __forceinline__ SchedSeq sched_seq(const int32_t* __restrict__ cu, const int32_t* __restrict__ seqused,
+                                              int i, int total_tokens) {
+  SchedSeq s;
+  s.r0 = min(max(cu[i], 0), total_tokens);
+  s.len = min(max(cu[i + 1] - s.r0, 0), total_tokens - s.r0);
+  s.nk = s.len <= 0 ? 0 : (seqused ? min(max(seqused[i], 0), s.len) : s.len);
+  return s;
+}
+
 // One workgroup.  count <- number of tiles, list[0..count) <- tiles.  `cap`
 // bounds the list (total_tokens/128 + batch always suffices).
 __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* __restrict__ cu,
                                                                  const int32_t* __restrict__ seqused,
-                                                                 int batch, int32_t* count,
+                                                                 int batch, int total_tokens, int32_t* count,
                                                                  TileItem* list, int cap, uint32_t* feed_counters) {
   __shared__ int cursor[kSchedBuckets];
   const int tid = threadIdx.x;
@@ -31,18 +47,12 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   __syncthreads();
   // The thread's first sequence stays in registers for the second sweep (one memory
   // round trip less on the usual batch of at most 1024 sequences).
-  int r0_first = 0, len_first = 0, nk_first = 0;
+  SchedSeq first = {0, 0, 0};
   for (int i = tid; i < batch; i += kSchedThreads) {
-    const int r0 = cu[i];
-    const int len = cu[i + 1] - r0;
-    const int nk = len <= 0 ? 0 : (seqused ? min(max(seqused[i], 0), len) : len);
-    if (i == tid) {
-      r0_first = r0;
-      len_first = len;
-      nk_first = nk;
-    }
-    if (len <= 0) continue;
-    atomicAdd(&cursor[sched_bucket(nk)], (len + kTileRows - 1) / kTileRows);
+    const SchedSeq s = sched_seq(cu, seqused, i, total_tokens);
+    if (i == tid) first = s;
+    if (s.len <= 0) continue;
+    atomicAdd(&cursor[sched_bucket(s.nk)], (s.len + kTileRows - 1) / kTileRows);
   }
   __syncthreads();
   // exclusive prefix sum over the 128 buckets: two wavefronts scan 64 each, the
@@ -71,17 +81,12 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int32_t* 
   }
   __syncthreads();
   for (int i = tid; i < batch; i += kSchedThreads) {
-    int r0 = r0_first, len = len_first, nk = nk_first;
-    if (i != tid) {
-      r0 = cu[i];
-      len = cu[i + 1] - r0;
-      nk = len <= 0 ? 0 : (seqused ? min(max(seqused[i], 0), len) : len);
-    }
-    if (len <= 0) continue;
-    const int nt = (len + kTileRows - 1) / kTileRows;
-    int at = atomicAdd(&cursor[sched_bucket(nk)], nt);
+    const SchedSeq s = i == tid ? first : sched_seq(cu, seqused, i, total_tokens);
+    if (s.len <= 0) continue;
+    const int nt = (s.len + kTileRows - 1) / kTileRows;
+    const int at = atomicAdd(&cursor[sched_bucket(s.nk)], nt);
     for (int t = 0; t < nt; t++)
-      if (at + t < cap) list[at + t] = TileItem{r0, len, nk, t * kTileRows};
+      if (at + t < cap) list[at + t] = TileItem{s.r0, s.len, s.nk, t * kTileRows};
   }
 }
 
