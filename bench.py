@@ -24,16 +24,29 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0}   # MI355X dense MFMA, published
 HBM_GBS = 8000.0
-# HBM bytes per launch on workload 3 from rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs, scaled by
-# a plain-copy reference (factors 2.0 and 1.0); see profiles/fmha_kernels_bert_large_fwd_bwd.md
-# the same for the other --op modes on workload 3's shapes (profiles/*_kernels*.md)
+# HBM bytes per launch of the other --op modes on workload 3's shapes, from rocprofv3 FETCH_SIZE /
+# WRITE_SIZE counter runs scaled by a plain-copy reference (profiles/*_kernels*.md)
 MEASURED_TRAFFIC_OTHER_CFG3 = {"gather_rows": 32.9e6 + 32.3e6, "scatter_rows": 33.3e6 + 58.7e6,
                                "unpad_indices": 0.27e6 + 0.18e6,
                                "ln_fwd_kernel": 64.7e6 + 65.5e6,
                                "ln_bwd (rows + columns)": 65.3e6 + 67.0e6 + 2.1e6,
                                "embedding_bwd_window_kernel": 32.7e6 + 26.3e6}
-MEASURED_TRAFFIC_CFG3 = {"fmha_fwd_kernel": 97.3e6 + 33.3e6, "bwd_dq_kernel": 163.4e6 + 34.4e6,
-                         "bwd_dkv_kernel": 132.3e6 + 64.6e6}
+
+
+def stored_traffic(workload, kernel):
+    """HBM bytes per launch of an attention kernel from profiles/traffic.json (written by
+    paper_2208_08124_amd/profile_traffic.py from counter runs), or None if the file is
+    missing, is for another workload, or was measured on other kernel sources."""
+    from paper_2208_08124_amd import build
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as fh:
+            doc = json.load(fh)
+    except (OSError, ValueError):
+        return None
+    if doc.get("source_id") != build.source_id() or doc.get("workload") != workload:
+        return None
+    k = doc.get("kernels", {}).get(kernel)
+    return None if k is None else k["fetch_bytes"] + k["write_bytes"]
 
 
 def parse():
@@ -142,15 +155,33 @@ def main():
             self.fwd()      # builds the tile list, then the forward kernel
             self.bwd()      # reuses the list: dQ pass + dK/dV pass
 
+    def precondition(fn, seconds=0.5):
+        """Untimed steps for a fixed duration ahead of a timed region: a short run (the driver's
+        20 steps take 5 ms) otherwise measures the chip on its way up from idle clocks."""
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+
     def timed(fn, steps, warmup):
+        """Seconds per step by the wall clock over exactly `steps` steps after `warmup` untimed
+        ones; timed.events_ms holds the median and minimum of the same steps by HIP events."""
+        precondition(fn)
         for _ in range(warmup):
             fn()
         torch.cuda.synchronize()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
-        for _ in range(steps):
+        evs[0].record()
+        for i in range(steps):
             fn()
+            evs[i + 1].record()
         torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / steps
+        sec = (time.perf_counter() - t0) / steps
+        per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(steps))
+        timed.events_ms = {"median": round(per[len(per) // 2], 5), "min": round(per[0], 5)}
+        return sec
 
     d = Dev(b)
     warm_sec = timed(d.step, args.steps, args.warmup)
@@ -168,6 +199,7 @@ def main():
         turn[0] += 1
 
     sec = timed(cold_step, args.steps, max(args.warmup, n_sets))
+    step_events = dict(timed.events_ms)
 
     # per-kernel durations: HIP events on the launch stream between the three kernels of a
     # step (forward with the tile list already built, dQ pass, dK/dV pass), in step order and
@@ -222,7 +254,7 @@ def main():
     peak = PEAK_TFLOPS[dt]
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": peak,
                 "unit": "TFLOP/s", "frac": round(ach / peak, 4),
-                "traffic": MEASURED_TRAFFIC_CFG3.get(dom) if (args.config == 3 and not args.uniform) else None,
+                "traffic": None if args.uniform else stored_traffic(b["name"], dom),
                 "avg_launch_ms": round(k_ms[dom], 5),
                 "kernels_ms": {k: round(v, 5) for k, v in k_ms.items()},
                 "kernels_tflops": {k: round(k_fl[k] / (k_ms[k] * 1e-3) / 1e12, 2) for k in k_ms},
@@ -234,6 +266,7 @@ def main():
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec * 1e3, 5),
+        "ms_per_step_events": step_events,   # the timed steps again, one by one, by HIP events
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dt, "data": "synthetic",
         "config": {"workload": b["name"], "baseline_config": args.config, "sequences": int(b["batch"]),
@@ -282,9 +315,26 @@ def main():
         sub_cu = wl.cu_from_lengths(lengths[pick])
         x = {nm: wl.bits_to_f64(b[nm][rows], dt) for nm in ("q", "k", "v", "do")}
         t0 = time.perf_counter()
-        oracle.fwd(x["q"], x["k"], x["v"], sub_cu, b["scale"])
-        oracle.bwd(x["q"], x["k"], x["v"], x["do"], sub_cu, b["scale"])
+        o_ref, _ = oracle.fwd(x["q"], x["k"], x["v"], sub_cu, b["scale"])
+        g_ref = oracle.bwd(x["q"], x["k"], x["v"], x["do"], sub_cu, b["scale"])
         csec = time.perf_counter() - t0
+        # one more step (outside every timed region; without dropout, which the oracle call
+        # above does not have either), against the oracle's results for the same sequences:
+        # what the parity tests assert, as achieved numbers
+        from oracle.parity import gradient_errors
+        Dev.drop = None
+        d.step()
+        torch.cuda.synchronize()
+        ridx = torch.from_numpy(rows).cuda()
+        f64 = lambda t: t[ridx].double().cpu().numpy()
+        parity = {"sequences": len(pick), "o_max_abs": float(np.abs(f64(d.o) - o_ref).max())}
+        for nm, got, want in zip(("dq", "dk", "dv"), (d.dq, d.dk, d.dv), g_ref):
+            rel, fro = gradient_errors(f64(got), want, sub_cu)
+            parity[nm + "_worst_sequence_rel"] = round(rel, 6)
+            parity[nm + "_frobenius_rel"] = round(fro, 6)
+        parity["o_max_abs"] = round(parity["o_max_abs"], 6)
+        parity["bar"] = "o_max_abs <= 5e-3 (+ half a bf16 ulp of O for bf16), gradients <= 1e-2"
+        out["parity"] = parity
         sub_fl = 14.0 * float((lengths[pick].astype(np.float64) ** 2).sum()) * H * 64
         out["cpu_baseline"] = {"value": round(sub_fl / csec / 1e12, 6), "unit": "TFLOP/s",
                                "cores": oracle.num_threads(), "kind": "oracle",

@@ -85,6 +85,14 @@ static double softmax_row(const double *q, const double *kbase, int64_t kstride,
   return m + log(z);
 }
 
+/* Keys attended in sequence i: all L, or the caller's count clamped to [0, L] (a count beyond
+ * the sequence, like a negative one, is a statement about padding, not a request to read
+ * past the end). */
+static int attended_keys(const int32_t *seqused, int i, int L) {
+  if (!seqused) return L;
+  return seqused[i] < 0 ? 0 : seqused[i] > L ? L : seqused[i];
+}
+
 static int fwd_impl(const double *q, const double *k, const double *v, const int32_t *cu,
                     const int32_t *seqused, int B, int H, int D, double scale, const uint8_t *keep,
                     const int64_t *keep_off, double keep_scale, double *o, double *lse) {
@@ -96,7 +104,7 @@ static int fwd_impl(const double *q, const double *k, const double *v, const int
   for (int i = 0; i < B; i++) {
     for (int h = 0; h < H; h++) {
       const int r0 = cu[i], L = cu[i + 1] - cu[i];
-      const int nk = seqused ? seqused[i] : L;
+      const int nk = attended_keys(seqused, i, L);
       if (L == 0) continue;
       double *p = (double *)malloc(sizeof(double) * (size_t)(nk > 0 ? nk : 1));
       if (!p) {
@@ -152,7 +160,7 @@ static int bwd_impl(const double *q, const double *k, const double *v, const dou
   for (int i = 0; i < B; i++) {
     for (int h = 0; h < H; h++) {
       const int r0 = cu[i], L = cu[i + 1] - cu[i];
-      const int nk = seqused ? seqused[i] : L;
+      const int nk = attended_keys(seqused, i, L);
       if (L == 0) continue;
       const int64_t hb = (int64_t)h * D;
       double *p = (double *)malloc(sizeof(double) * (size_t)(2 * (nk > 0 ? nk : 1)));

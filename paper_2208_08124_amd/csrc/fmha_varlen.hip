@@ -65,12 +65,14 @@ Workspace carve(void* base, int64_t batch, int64_t total_tokens, int64_t heads) 
   const size_t stat_bytes = round_up(sizeof(float) * ((size_t)total_tokens * (size_t)heads + 1), kAlign);
   w.lse2_off = w.dsum_off + stat_bytes;
   w.bytes_bwd = w.lse2_off + stat_bytes;
-  char* b = static_cast<char*>(base);
-  w.count = reinterpret_cast<int32_t*>(b + w.count_off);
-  w.feed = reinterpret_cast<uint32_t*>(b + w.feed_off);
-  w.list = reinterpret_cast<fmha::TileItem*>(b + w.list_off);
-  w.dsum = reinterpret_cast<float*>(b + w.dsum_off);
-  w.lse2 = reinterpret_cast<float*>(b + w.lse2_off);
+  // (base is null when only the sizes are wanted: no pointer arithmetic on it then)
+  const uintptr_t b = reinterpret_cast<uintptr_t>(base);
+  auto at = [b](size_t off) { return b ? reinterpret_cast<void*>(b + off) : nullptr; };
+  w.count = static_cast<int32_t*>(at(w.count_off));
+  w.feed = static_cast<uint32_t*>(at(w.feed_off));
+  w.list = static_cast<fmha::TileItem*>(at(w.list_off));
+  w.dsum = static_cast<float*>(at(w.dsum_off));
+  w.lse2 = static_cast<float*>(at(w.lse2_off));
   return w;
 }
 

@@ -74,17 +74,17 @@ def check(b, db, p, seed):
     # remains is that rounding - up to 1e-2 absolute in bfloat16, which would be measured
     # against the small gradients of long sequences.  test_single_token_sequences_under_dropout
     # bounds those rows by what the rounding of O allows.
-    lens = np.diff(cu)
-    multi = np.repeat(lens > 1, lens)
+    # Every sequence is measured on its own scale (max-abs error over its rows / max |reference|
+    # over the same rows, floored at G_FLOOR).
     for name, got, want in zip(("dq", "dk", "dv"), (db.dq, db.dk, db.dv), ref):
         g = to_f64(got)
         assert not np.isnan(g).any(), f"{name}: rows left unwritten"
-        if name != "dv":
-            g, want = g[multi], want[multi]
-        if g.size == 0:
-            continue
-        rel = np.abs(g - want).max() / max(np.abs(want).max(), G_FLOOR)
-        assert rel <= G_TOL, f"{name}: max-abs error / max|ref| = {rel:.3e}"
+        for i in range(len(cu) - 1):
+            a, e = int(cu[i]), int(cu[i + 1])
+            if e == a or (e - a == 1 and name != "dv"):
+                continue
+            rel = np.abs(g[a:e] - want[a:e]).max() / max(np.abs(want[a:e]).max(), G_FLOOR)
+            assert rel <= G_TOL, f"{name}, sequence {i}: max-abs error / max|ref| = {rel:.3e}"
 
 
 def run(b, p, seed, need_bwd=True):
@@ -111,8 +111,15 @@ def test_dropout_fwd_bwd_ragged(lengths, p, dtype):
 def test_single_token_sequences_under_dropout(dtype):
     """L = 1: P = 1, so O = V / (1-p) if the one element is kept and 0 if not, dV likewise
     from dO, and dQ = dK = 0 in exact arithmetic.  The kernels form D from the stored
-    (16-bit) O, so dQ and dK carry that rounding and nothing else:
-    |dQ| <= |scale| max|K| sum_c |dO_c| * (half an ulp of O), and the same with Q for dK."""
+    (16-bit) O, so dS = dP - D is what that rounding leaves:
+        |dS| <= sum_c |dO_c| * (half an ulp of O_c)  +  fp32 effects,
+    and |dQ| <= |scale| max|K| |dS|, the same with Q for dK.  The fp32 effects (two 64-term
+    dot products accumulated in fp32, relative error <= 64 * 2^-24 each, and the exponent's
+    argument, |P - 1| <= 3 * 2^-24 |S log2 e|) are bounded by 2.2e-5 * sum_c |dO_c O_c|, which
+    is at most 2.2e-5 * 2^12 = 9 % of the first term (|O| / half-ulp(O) <= 2^12 for f16, 2^9
+    for bf16); the 16-bit roundings of dS and of the stored dQ add under 1 %.  Hence the
+    factor 1.15 below and no additive term: a dropped element has O = 0, D = dP = 0 and an
+    exactly zero gradient."""
     n, h, p, seed = 40, 2, 0.5, 77
     b = wl.make_batch([1] * n, h, dtype, seed=11)
     db = DeviceBatch(b, True)
@@ -129,7 +136,7 @@ def test_single_token_sequences_under_dropout(dtype):
     dv_want = x["do"] * (keep * c)[:, :, None]
     assert (np.abs(dv - dv_want) <= ulp_half(dv_want, dtype) * 1.01 + 1e-12).all()
     half_ulp_o = ulp_half(o_want, dtype).max(axis=2)                       # [n, h]
-    slack = abs(b["scale"]) * np.abs(x["do"]).sum(axis=2) * half_ulp_o * 1.05 + 1e-3
+    slack = abs(b["scale"]) * np.abs(x["do"]).sum(axis=2) * half_ulp_o * 1.15
     assert (np.abs(dq) <= (np.abs(x["k"]).max(axis=2) * slack)[:, :, None]).all()
     assert (np.abs(dk) <= (np.abs(x["q"]).max(axis=2) * slack)[:, :, None]).all()
 

@@ -312,6 +312,21 @@ def test_seqused_zero_row_convention():
         assert np.abs(g).max() == 0
 
 
+def test_seqused_is_clamped_to_the_sequence():
+    """A key count beyond the sequence means "all keys", a negative one "none": the count
+    describes padding, it never makes the oracle read another sequence's rows (the two
+    sequences here would otherwise see each other)."""
+    q, k, v, do = (rand(9, 2, 8) for _ in range(4))
+    cu = cu_of([4, 5])
+    full = oracle.fwd(q, k, v, cu, 0.3), oracle.bwd(q, k, v, do, cu, 0.3)
+    over = oracle.fwd(q, k, v, cu, 0.3, seqused=[7, 500]), oracle.bwd(q, k, v, do, cu, 0.3, seqused=[7, 500])
+    for a, b in zip(full[0] + full[1], over[0] + over[1]):
+        assert np.array_equal(a, b)
+    none = oracle.fwd(q, k, v, cu, 0.3, seqused=[-1, 5])
+    assert np.abs(none[0][:4]).max() == 0 and np.all(np.isneginf(none[1][:, :4]))
+    assert np.array_equal(none[0][4:], full[0][0][4:])
+
+
 # --------------------------------------------------------------------------
 # library special case: scipy's softmax + numpy matmul per (sequence, head)
 # --------------------------------------------------------------------------
