@@ -547,6 +547,30 @@ def bench_embedding(args, torch, fmha, wl):
         return sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
 
     ms_die, ms_plain, ms_nodie = timed_events(False), timed_events(True), timed_events(False, True)
+
+    # the variant without atomics: the sort (once per batch of indices) and the backward call
+    # that uses it, timed separately
+    ws = [torch.empty(fmha.fmha_embedding_sort_workspace_size(t, hid), dtype=torch.uint8, device="cuda") for _ in sets]
+
+    def timed_sorted(which):
+        def call(i):
+            x = sets[i % n_sets]
+            if which == "sort":
+                fmha.fmha_embedding_sort(x.ids, hid, vocab, ws[i % n_sets])
+            else:
+                fmha.fmha_embedding_bwd_sorted(x.dy, ws[i % n_sets], x.dw)
+        for i in range(n_sets):
+            call(i)
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        for i in range(args.steps):
+            evs[i][0].record()
+            call(i)
+            evs[i][1].record()
+        torch.cuda.synchronize()
+        return sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+
+    ms_sort, ms_sorted = timed_sorted("sort"), timed_sorted("bwd")
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -570,7 +594,14 @@ def bench_embedding(args, torch, fmha, wl):
                         "kernels_ms": {"embedding_bwd_window_kernel (default: duplicates merged, split by die)": round(ms_die, 5),
                                        "embedding_bwd_window_kernel (duplicates merged, no die split)": round(ms_nodie, 5),
                                        "embedding_bwd_kernel (plain: one token per wavefront)": round(ms_plain, 5)},
-                        "packed_atomics_per_s": round(t * hid / 2 / (ms_die * 1e-3), 1)}}
+                        "packed_atomics_per_s": round(t * hid / 2 / (ms_die * 1e-3), 1)},
+           "sorted_variant": {"what": "fmha_embedding_sort once per batch of indices, then fmha_embedding_bwd_sorted: "
+                                      "fp32 sums in sorted order, one write per weight row, no atomics",
+                              "sort_ms": round(ms_sort, 5), "backward_ms": round(ms_sorted, 5),
+                              "rows_per_s": round(t / (ms_sorted * 1e-3), 1),
+                              "rows_per_s_with_sort": round(t / ((ms_sorted + ms_sort) * 1e-3), 1),
+                              "hbm_GBs": round(alg / (ms_sorted * 1e-3) / 1e9, 1),
+                              "hbm_frac": round(alg / (ms_sorted * 1e-3) / 1e9 / HBM_GBS, 4)}}
     if not args.no_cpu_baseline:
         from oracle import embedding as oemb
         n = min(t, 20000)

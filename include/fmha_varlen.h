@@ -310,6 +310,33 @@ int fmha_embedding_bwd(const void* dy, const int32_t* indices, const int32_t* n_
                        int32_t hidden, int32_t vocab, int32_t padding_idx, int32_t dtype,
                        uint32_t flags, void* dw, void* stream);
 
+/* The same without atomics, in two calls, for callers that know the indices before the
+ * gradient arrives (the paper computes its index tensors once per mini-batch, Section
+ * IV-B-2; Section IV-C-3 names the colliding additions as the cost of this step):
+ *   fmha_embedding_sort        orders the token positions by index (a stable radix sort on
+ *                              the device) into `workspace`;
+ *   fmha_embedding_bwd_sorted  sums the gradient rows of every index in that order in fp32,
+ *                              adds the weight row that is there (unless FMHA_EMB_ZERO_FIRST,
+ *                              which clears all of dw first) and writes the row once, rounded
+ *                              once to the 16-bit type.
+ * Tokens are skipped as in fmha_embedding_bwd (index outside [0, vocab), index ==
+ * padding_idx, position >= *n_rows).  Every weight row has one writer and every sum a fixed
+ * order, so results are identical from run to run, and a row that receives n gradient rows
+ * carries the error of an fp32 sum of n terms plus one rounding.
+ *   workspace : device, 256-byte aligned, fmha_embedding_sort_workspace_size(rows, hidden)
+ *               bytes; written by the sort, read and written by the backward call (partial
+ *               sums), reusable for any number of backward calls on the same indices.
+ * rows, hidden, vocab of the two calls must agree (the workspace layout depends on rows and
+ * hidden); FMHA_EMB_PLAIN_SPLIT / NO_DIE_SPLIT have no meaning here and are rejected.
+ * Errors as above, FMHA_ERR_WORKSPACE for a missing, misaligned or short workspace. */
+size_t fmha_embedding_sort_workspace_size(int32_t rows, int32_t hidden);
+int fmha_embedding_sort(const int32_t* indices, const int32_t* n_rows, int32_t rows, int32_t hidden,
+                        int32_t vocab, int32_t padding_idx, void* workspace, size_t workspace_bytes,
+                        void* stream);
+int fmha_embedding_bwd_sorted(const void* dy, void* workspace, size_t workspace_bytes, int32_t rows,
+                              int32_t hidden, int32_t vocab, int32_t dtype, uint32_t flags, void* dw,
+                              void* stream);
+
 /* Number of 128-row tiles the schedule holds at most for this shape (host
  * arithmetic), and a device-to-host-free way for tests to locate the tile list
  * inside the workspace: the list starts at byte offset *list_offset and holds

@@ -58,7 +58,6 @@ struct BwdArgs {
   int64_t q_stride, k_stride, v_stride, o_stride, do_stride, dq_stride, dk_stride, dv_stride;
 };
 
-#ifdef __HIPCC__
 // The tile list and its count were written by an earlier kernel and are only
 // read here.  Reading them through the constant address space lets the compiler
 // use scalar loads (wave-uniform, tracked by their own counter) instead of vector
@@ -70,6 +69,5 @@ __device__ __forceinline__ TileItem load_tile(const Problem& pb, int i) {
   return TileItem{p[0], p[1], p[2], p[3]};
 }
 __device__ __forceinline__ int tile_count(const Problem& pb) { return *(ConstInt)(uintptr_t)pb.n_tiles; }
-#endif
 
 }  // namespace fmha

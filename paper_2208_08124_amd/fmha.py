@@ -29,7 +29,8 @@ EXPORTS = ("fmha_varlen_workspace_size", "fmha_varlen_fwd", "fmha_varlen_bwd",
            "fmha_varlen_fwd_dropout", "fmha_varlen_bwd_dropout", "fmha_dropout_keep_mask",
            "fmha_unpad_indices_host", "fmha_unpad_indices", "fmha_gather_rows", "fmha_scatter_rows",
            "fmha_dropout_add_ln_fwd", "fmha_dropout_add_ln_bwd", "fmha_dropout_add_ln_bwd_workspace_size",
-           "fmha_embedding_bwd",
+           "fmha_embedding_bwd", "fmha_embedding_sort_workspace_size", "fmha_embedding_sort",
+           "fmha_embedding_bwd_sorted",
            "fmha_varlen_schedule_info", "fmha_last_error")
 
 
@@ -114,6 +115,12 @@ def lib():
         L.fmha_dropout_add_ln_bwd_workspace_size.restype = ctypes.c_size_t
         L.fmha_embedding_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_uint32, vp, vp]
         L.fmha_embedding_bwd.restype = ctypes.c_int
+        L.fmha_embedding_sort_workspace_size.argtypes = [i32, i32]
+        L.fmha_embedding_sort_workspace_size.restype = ctypes.c_size_t
+        L.fmha_embedding_sort.argtypes = [vp, vp, i32, i32, i32, i32, vp, ctypes.c_size_t, vp]
+        L.fmha_embedding_sort.restype = ctypes.c_int
+        L.fmha_embedding_bwd_sorted.argtypes = [vp, vp, ctypes.c_size_t, i32, i32, i32, i32, ctypes.c_uint32, vp, vp]
+        L.fmha_embedding_bwd_sorted.restype = ctypes.c_int
         L.fmha_varlen_schedule_info.argtypes = [ctypes.c_int32] * 3 + [ctypes.POINTER(ctypes.c_size_t)] * 2
         L.fmha_varlen_schedule_info.restype = ctypes.c_int32
         L.fmha_last_error.restype = ctypes.c_char_p
@@ -352,6 +359,29 @@ def fmha_dropout_add_ln_bwd(dy, z, mu, rstd, gamma, eps, dx, dresidual, dgamma, 
                                          None if dresidual is None else dresidual.data_ptr(),
                                          dgamma.data_ptr(), dbeta.data_ptr(), workspace.data_ptr(),
                                          workspace.numel() * workspace.element_size(), _stream()))
+
+
+def fmha_embedding_sort_workspace_size(rows: int, hidden: int) -> int:
+    return int(lib().fmha_embedding_sort_workspace_size(rows, hidden))
+
+
+def fmha_embedding_sort(indices, hidden, vocab, workspace, *, padding_idx=-1, n_rows=None):
+    """Orders the token positions by index into `workspace` (uint8 device tensor of
+    fmha_embedding_sort_workspace_size(rows, hidden) bytes) for fmha_embedding_bwd_sorted."""
+    assert indices.dtype == torch.int32 and indices.is_cuda and indices.dim() == 1
+    _check(lib().fmha_embedding_sort(indices.data_ptr(), None if n_rows is None else n_rows.data_ptr(),
+                                     indices.numel(), int(hidden), int(vocab), int(padding_idx), workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), _stream()))
+
+
+def fmha_embedding_bwd_sorted(dy, workspace, dw, *, zero_first=False):
+    """dw[i] += sum of the rows dy[t] with indices[t] = i, in the order fmha_embedding_sort left in
+    `workspace`: fp32 sums, one write per weight row, no atomics."""
+    assert dy.dim() == 2 and dw.dim() == 2 and dy.is_contiguous() and dw.is_contiguous() and dy.dtype == dw.dtype
+    _check(lib().fmha_embedding_bwd_sorted(dy.data_ptr(), workspace.data_ptr(),
+                                           workspace.numel() * workspace.element_size(), dy.shape[0], dy.shape[1],
+                                           dw.shape[0], _dtype_code(dy), FMHA_EMB_ZERO_FIRST if zero_first else 0,
+                                           dw.data_ptr(), _stream()))
 
 
 def fmha_embedding_bwd(dy, indices, dw, *, padding_idx=-1, n_rows=None, zero_first=False, plain_split=False,

@@ -28,6 +28,10 @@ def check_forward(b, db):
     extra = ulp_half(o_ref, b["dtype"]) if b["dtype"] == "bf16" else 0.0
     err = np.abs(o - o_ref)
     assert (err <= O_TOL + extra).all(), f"max |O - O_ref| = {err.max():.3e}"
+    # the allowance for bf16 storage is only needed from |O| = 1 on: below, half an ulp is
+    # under 2e-3 and the plain bar holds for every element
+    small = np.abs(o_ref) < 1.0
+    assert (err[small] <= O_TOL).all(), f"max |O - O_ref| where |O_ref| < 1 = {err[small].max():.3e}"
     fin = np.isfinite(lse_ref)
     assert np.array_equal(np.isfinite(lse), fin)
     assert np.abs(lse[fin] - lse_ref[fin]).max() <= 1e-3 * max(1.0, np.abs(lse_ref[fin]).max())
