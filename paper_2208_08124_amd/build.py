@@ -22,17 +22,19 @@ def sources():
     return [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith(".hip")]
 
 
+ATTENTION_SOURCES = ("fmha_varlen.hip", "fwd64_kernel.h", "fwd_kernel.h", "bwd_kernels.h", "mfma_tiles.h",
+                     "kernel_args.h", "item_feed.h", "schedule.h", "dropout.h")
+
+
 def source_id() -> str:
-    """Identifies what the library is built from: a hash over the kernel sources, the public
-    header and the compiler flags.  Measurements that are stored in the repository (HBM traffic
+    """Identifies what the attention kernels are built from: a hash over their sources and
+    the compiler flags.  Measurements of them that are stored in the repository (HBM traffic
     from counter runs) carry it, so that a stored figure is never quoted for other kernels."""
     import hashlib
     h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
-    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".h"))]
-    files.append(os.path.join(os.path.dirname(HERE), "include", "fmha_varlen.h"))
-    for f in files:
-        h.update(os.path.basename(f).encode())
-        with open(f, "rb") as fh:
+    for name in ATTENTION_SOURCES:
+        h.update(name.encode())
+        with open(os.path.join(CSRC, name), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
 

@@ -12,8 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# FMHA_VARLEN_LIB points at another build of the same library (kernel studies)
-LIB_PATH = os.environ.get("FMHA_VARLEN_LIB") or os.path.join(_HERE, "libfmha_varlen.so")
+LIB_PATH = os.path.join(_HERE, "libfmha_varlen.so")
 
 FMHA_OK, FMHA_ERR_INVALID_ARG, FMHA_ERR_UNSUPPORTED, FMHA_ERR_WORKSPACE, FMHA_ERR_HIP = range(5)
 FMHA_F16, FMHA_BF16 = 0, 1
