@@ -422,6 +422,33 @@ def test_hand_out_counters_are_left_zero():
     assert not db.ws[feed].any() and torch.equal(db.o, first)
 
 
+def test_device_arrays_that_disagree_with_the_sizes_stay_in_range():
+    """Without a host copy the prefix sums are read on the device only.  Entries that decrease
+    or point beyond total_tokens are clamped into the packed tensors when the tile list is built
+    (wrong numbers for those sequences, never an address out of range): the call completes, and
+    a well-formed sequence beside them is still computed correctly."""
+    b = wl.make_batch([50, 70, 40, 30], 2, "f16", seed=91)
+    db = DeviceBatch(b, True)
+    t = b["total_tokens"]
+    # sequence 2 ends before it starts (dropped), sequence 3 starts inside sequence 1 and ends far
+    # beyond the tensors (clamped to the rows that exist); sequence 0 is untouched by either
+    db.cu = torch.tensor([0, 50, 120, 90, 10 ** 6], dtype=torch.int32, device="cuda")
+    db.o.fill_(0), db.dq.fill_(0), db.dk.fill_(0), db.dv.fill_(0)
+    db.fwd()
+    db.bwd(reuse_schedule=True)
+    torch.cuda.synchronize()
+    first = wl.make_batch([50], 2, "f16", seed=91)
+    for n in ("q", "k", "v", "do"):
+        first[n] = b[n][:50]
+    x = oracle_inputs(first)
+    o_ref, _ = oracle.fwd(x["q"], x["k"], x["v"], first["cu_seqlens"], first["scale"])
+    assert np.abs(to_f64(db.o[:50]) - o_ref).max() <= O_TOL
+    g_ref = oracle.bwd(x["q"], x["k"], x["v"], x["do"], first["cu_seqlens"], first["scale"])
+    for got, want in zip((db.dq, db.dk, db.dv), g_ref):
+        rel, fro = gradient_errors(to_f64(got[:50]), want, first["cu_seqlens"])
+        assert rel <= G_TOL and fro <= G_TOL
+
+
 def test_two_runs_are_bit_identical():
     b = wl.make_workload(4)
     a_, b_ = DeviceBatch(b, True), DeviceBatch(b, True)
