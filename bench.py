@@ -237,6 +237,26 @@ def main():
         x.fwd(reuse=True)
         x.bwd()
     reuse_sec = timed(reuse_step, args.steps, n_sets)
+    # the same cold rotation with every buffer set's step captured once in a HIP graph and
+    # replayed: what the launch gaps between the four kernels of a step cost in eager mode
+    graph_replay = None
+    try:
+        graphs = []
+        for x in sets:
+            gph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gph):
+                x.step()
+            graphs.append(gph)
+
+        def graph_step():
+            graphs[turn[0] % n_sets].replay()
+            turn[0] += 1
+        gsec = timed(graph_step, args.steps, n_sets)
+        graph_replay = {"ms_per_step": round(gsec * 1e3, 5), "value": round(fl_all / gsec / 1e12, 3),
+                        "ms_per_step_events": dict(timed.events_ms)}
+        del graphs
+    except RuntimeError as e:   # capture not available: report why, keep the eager figures
+        graph_replay = {"error": str(e)[:200]}
     with_dropout = None
     if args.dropout == 0:
         # the same cold rotation through the dropout entry points, p = 0.1 (BERT's setting)
@@ -284,6 +304,7 @@ def main():
                   "warm_ms_per_step": round(warm_sec * 1e3, 5),
                   "warm_value": round(fl_all / warm_sec / 1e12, 3)},
         "roofline": roofline,
+        "graph_replay": graph_replay,
     }
     if args.dropout > 0:
         out["config"]["dropout_p"] = args.dropout
